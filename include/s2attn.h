@@ -1,0 +1,141 @@
+/* s2attn.h -- C ABI of the MI355X (gfx950) shifted sparse attention library.
+ *
+ * The operation is S2-Attn of LongLoRA (arXiv 2309.12307), Section 3.2 and
+ * Algorithm 1: the N tokens are cut into N/G groups of G tokens; for the second
+ * contiguous half of the query heads the partition is shifted by G/2 tokens with
+ * wrap-around (token t sits at rolled position (t - G/2) mod N); softmax
+ * attention (Equation 1, with the 1/sqrt(D) scale and the causal mask of a
+ * standard decoder self-attention, both in the rolled in-group index) runs inside
+ * every group; outputs land at their original token rows.  No rolled copy of any
+ * tensor is made: the roll only changes which rows a tile reads and writes.
+ *
+ * Conventions common to every call
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or keeps them.  `stream` is a hipStream_t passed as
+ *     void* (NULL = the default stream).  Calls only enqueue work and return.
+ *   - Layouts are contiguous row-major: q, o, dout, dq are (B, N, H, D);
+ *     k, v, dk, dv are (B, N, Hkv, D); lse is (B, H, N) fp32 and holds the natural
+ *     log of the sum of exp of the scaled, masked scores of each ORIGINAL token.
+ *   - Grouped-query attention: query head h reads kv head h / (H/Hkv); whether a
+ *     head is shifted is a property of the query head; dk, dv sum over the query
+ *     heads that share a kv head.
+ *   - Return value: 0 (S2ATTN_OK) or a negative S2ATTN_ERR_* code.  On error
+ *     nothing has been launched.  The library has no mutable global state;
+ *     calls are re-entrant and may be issued from several host threads.
+ *   - Tensor pointers must be 16-byte aligned.
+ */
+#ifndef S2ATTN_H
+#define S2ATTN_H
+
+#include <stddef.h>
+
+#if defined(__GNUC__)
+#define S2ATTN_API __attribute__((visibility("default")))
+#else
+#define S2ATTN_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  S2ATTN_OK = 0,
+  S2ATTN_ERR_NULL = -1,        /* a required pointer is NULL */
+  S2ATTN_ERR_ALIGN = -2,       /* a tensor pointer is not 16-byte aligned */
+  S2ATTN_ERR_DIM = -3,         /* B, N, H, Hkv, D or G is not positive */
+  S2ATTN_ERR_GROUP = -4,       /* N % G != 0, or G odd, or shift outside [0, G) */
+  S2ATTN_ERR_HEADS = -5,       /* H odd (half of the heads shift), or H % Hkv != 0 */
+  S2ATTN_ERR_HEADDIM = -6,     /* D not supported: fp32 needs D in {64,128}; bf16 needs D == 128 */
+  S2ATTN_ERR_TILE = -7,        /* bf16 path: G must be a multiple of 128 */
+  S2ATTN_ERR_WORKSPACE = -8,   /* backward workspace missing or too small */
+  S2ATTN_ERR_DTYPE = -9,       /* unknown dtype / rule / variant value */
+  S2ATTN_ERR_DEVICE = -10,     /* current device is not gfx950 */
+  S2ATTN_ERR_LAUNCH = -11,     /* HIP reported a launch error */
+  S2ATTN_ERR_TOO_LARGE = -12   /* tensor too large for the index arithmetic, or over a fixed limit */
+};
+
+enum { S2ATTN_BF16 = 0, S2ATTN_F32 = 1 };
+
+/* Which query heads use the shifted partition (Section 3.2; the attention-pattern
+ * ablation of Section 4.3 uses the other two). */
+enum {
+  S2ATTN_SHIFT_SECOND_HALF = 0, /* heads [H/2, H): the method as published */
+  S2ATTN_SHIFT_NONE = 1,        /* no head shifts ("pattern 1" only; with G == N: full causal attention) */
+  S2ATTN_SHIFT_ALL = 2          /* every head shifts ("pattern 2" only) */
+};
+
+/* Treatment of the wrap-around group of shifted heads (last `shift` tokens
+ * followed by the first `shift` tokens; Appendix B.3). */
+enum {
+  S2ATTN_WRAP_JOINT = 0,  /* one causal group: the paper's default method */
+  S2ATTN_WRAP_SPLIT = 2   /* "Variant 2": the two halves are separate groups */
+};
+
+typedef struct s2attn_params {
+  /* forward: q, k, v in; o, lse out.  backward: q, k, v, o, dout, lse in; dq, dk, dv out. */
+  const void* q;
+  const void* k;
+  const void* v;
+  void* o;            /* written by forward, read by backward */
+  float* lse;         /* written by forward, read by backward */
+  const void* dout;   /* backward only */
+  void* dq;           /* backward only, overwritten */
+  void* dk;           /* backward only, overwritten */
+  void* dv;           /* backward only, overwritten */
+  void* workspace;    /* backward only: >= s2attn_bwd_workspace_bytes(...) bytes, 256-byte aligned */
+  size_t workspace_bytes;
+  int B, N, H, Hkv, D, G;
+  int dtype;          /* S2ATTN_BF16 or S2ATTN_F32: element type of q,k,v,o,dout,dq,dk,dv */
+  int shift;          /* tokens; negative = G/2 (the paper's value) */
+  int shift_rule;     /* S2ATTN_SHIFT_* */
+  int wrap_variant;   /* S2ATTN_WRAP_* */
+  float scale;        /* softmax scale; <= 0 means 1/sqrt(D) */
+} s2attn_params;
+
+/* Pure host check of a parameter block (pointers, alignment, shapes, workspace
+ * size when `backward` is non-zero).  Touches no GPU state. */
+S2ATTN_API int s2attn_check_args(const s2attn_params* p, int backward);
+
+/* Bytes of device workspace the backward needs: the fp32 row term
+ * delta[b,h,t] = sum_d dout*o, plus fp32 partial dk/dv when a kv head serves both
+ * shifted and unshifted query heads (odd Hkv under the second-half rule). */
+S2ATTN_API size_t s2attn_bwd_workspace_bytes(int B, int N, int H, int Hkv, int D, int G, int dtype);
+
+/* Forward of Algorithm 1, bf16 tensors, fp32 accumulation, default shift G/2 on
+ * heads [H/2, H), scale 1/sqrt(D). */
+S2ATTN_API int s2attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+               int B, int N, int H, int Hkv, int D, int G, void* stream);
+
+/* Backward of the same map: recomputes P from lse (softmax-Jacobian form
+ * dS = P * (dP - delta)); overwrites dq, dk, dv. */
+S2ATTN_API int s2attn_bwd(const void* q, const void* k, const void* v, const void* o,
+               const void* dout, const float* lse, void* dq, void* dk, void* dv,
+               void* workspace, size_t workspace_bytes,
+               int B, int N, int H, int Hkv, int D, int G, void* stream);
+
+/* Same two calls with fp32 tensors and fp32 arithmetic throughout. */
+S2ATTN_API int s2attn_fwd_f32(const float* q, const float* k, const float* v, float* o, float* lse,
+                   int B, int N, int H, int Hkv, int D, int G, void* stream);
+S2ATTN_API int s2attn_bwd_f32(const float* q, const float* k, const float* v, const float* o,
+                   const float* dout, const float* lse, float* dq, float* dk, float* dv,
+                   void* workspace, size_t workspace_bytes,
+                   int B, int N, int H, int Hkv, int D, int G, void* stream);
+
+/* General forms: dtype, shift amount, which heads shift (Section 4.3 ablation
+ * patterns), wrap-group variant (Appendix B.3) and scale come from the block. */
+S2ATTN_API int s2attn_fwd_ex(const s2attn_params* p, void* stream);
+S2ATTN_API int s2attn_bwd_ex(const s2attn_params* p, void* stream);
+
+/* Static, never-freed message for a return code. */
+S2ATTN_API const char* s2attn_strerror(int code);
+
+/* Effective FLOPs of one layer counting only in-group causal (query, key) pairs
+ * (Equation 1 restricted to the groups of Section 3.2): 4*D per pair forward,
+ * 10*D per pair backward.  pass: 0 = forward, 1 = backward, 2 = both. */
+S2ATTN_API double s2attn_effective_flops(int B, int N, int H, int D, int G, int pass);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S2ATTN_H */

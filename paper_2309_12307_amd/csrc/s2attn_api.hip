@@ -1,0 +1,234 @@
+// Host side of the C ABI declared in include/s2attn.h: argument checks, workspace
+// layout, translation of the public parameter block into the kernels' argument
+// block, and kernel launches.  Nothing here allocates device memory.
+#include "s2attn.h"
+
+#include <atomic>
+#include <cmath>
+#include <cstring>
+
+#include "s2attn_device.h"
+#include "s2attn_launch.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// First head that uses the shifted partition under a rule (Algorithm 1 shifts the
+// second chunk of chunk(2, head axis)).
+int shifted_from(int rule, int H, int shift) {
+  if (shift == 0) return H;
+  switch (rule) {
+    case S2ATTN_SHIFT_SECOND_HALF: return H / 2;
+    case S2ATTN_SHIFT_NONE: return H;
+    default: return 0;
+  }
+}
+
+int resolved_shift(const s2attn_params* p) { return p->shift < 0 ? p->G / 2 : p->shift; }
+
+// A kv head is "mixed" when its query heads fall on both sides of shifted_from.
+bool kv_heads_mixed(int H, int Hkv, int from) {
+  const int r = H / Hkv;
+  return from > 0 && from < H && (from % r) != 0;
+}
+
+size_t delta_bytes(int B, int N, int H) { return round_up((size_t)B * H * N * sizeof(float), kAlign); }
+
+size_t workspace_bytes_for(int B, int N, int H, int Hkv, int D, bool mixed) {
+  size_t w = delta_bytes(B, N, H);
+  if (mixed) w += round_up((size_t)4 * B * N * Hkv * D * sizeof(float), kAlign);
+  return w;
+}
+
+int check_common(const s2attn_params* p, int backward) {
+  if (!p) return S2ATTN_ERR_NULL;
+  if (p->dtype != S2ATTN_BF16 && p->dtype != S2ATTN_F32) return S2ATTN_ERR_DTYPE;
+  if (p->shift_rule < S2ATTN_SHIFT_SECOND_HALF || p->shift_rule > S2ATTN_SHIFT_ALL) return S2ATTN_ERR_DTYPE;
+  if (p->wrap_variant != S2ATTN_WRAP_JOINT && p->wrap_variant != S2ATTN_WRAP_SPLIT) return S2ATTN_ERR_DTYPE;
+  if (p->B <= 0 || p->N <= 0 || p->H <= 0 || p->Hkv <= 0 || p->D <= 0 || p->G <= 0) return S2ATTN_ERR_DIM;
+  if (p->N % p->G != 0 || p->G % 2 != 0) return S2ATTN_ERR_GROUP;
+  const int shift = resolved_shift(p);
+  if (shift < 0 || shift >= p->G) return S2ATTN_ERR_GROUP;
+  if (p->H % 2 != 0 || p->H % p->Hkv != 0) return S2ATTN_ERR_HEADS;
+  if (p->dtype == S2ATTN_F32) {
+    if (p->D != 64 && p->D != 128) return S2ATTN_ERR_HEADDIM;
+  } else {
+    if (p->D != 128) return S2ATTN_ERR_HEADDIM;
+    if (p->G % 128 != 0 || shift % 128 != 0) return S2ATTN_ERR_TILE;
+  }
+  // grid z carries batch * heads (* 2 classes); element offsets are 64-bit
+  if ((long long)p->B * p->H * 2 > 65535 || (long long)p->N / p->G > 65535) return S2ATTN_ERR_TOO_LARGE;
+  if ((double)p->B * p->N * p->H * p->D > 9.0e18 / 4) return S2ATTN_ERR_TOO_LARGE;
+
+  const void* need_fwd[] = {p->q, p->k, p->v, p->o, p->lse};
+  for (const void* x : need_fwd) {
+    if (!x) return S2ATTN_ERR_NULL;
+    if (!aligned16(x)) return S2ATTN_ERR_ALIGN;
+  }
+  if (backward) {
+    const void* need_bwd[] = {p->dout, p->dq, p->dk, p->dv};
+    for (const void* x : need_bwd) {
+      if (!x) return S2ATTN_ERR_NULL;
+      if (!aligned16(x)) return S2ATTN_ERR_ALIGN;
+    }
+    const bool mixed = kv_heads_mixed(p->H, p->Hkv, shifted_from(p->shift_rule, p->H, shift));
+    const size_t need = workspace_bytes_for(p->B, p->N, p->H, p->Hkv, p->D, mixed);
+    if (!p->workspace || p->workspace_bytes < need) return S2ATTN_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(p->workspace) & (kAlign - 1)) != 0) return S2ATTN_ERR_ALIGN;
+  }
+  return S2ATTN_OK;
+}
+
+// The kernels use gfx950-only instructions; refuse any other device.  The answer
+// per device ordinal is cached (0 unknown, 1 yes, 2 no).
+int check_device() {
+  static std::atomic<int> cache[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return S2ATTN_ERR_DEVICE;
+  int state = (dev >= 0 && dev < 64) ? cache[dev].load(std::memory_order_relaxed) : 0;
+  if (state == 0) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return S2ATTN_ERR_DEVICE;
+    state = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 2;
+    if (dev >= 0 && dev < 64) cache[dev].store(state, std::memory_order_relaxed);
+  }
+  return state == 1 ? S2ATTN_OK : S2ATTN_ERR_DEVICE;
+}
+
+s2::KArgs make_kargs(const s2attn_params* p) {
+  s2::KArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.q = p->q; a.k = p->k; a.v = p->v; a.o = p->o; a.lse = p->lse;
+  a.dout = p->dout; a.dq = p->dq; a.dk = p->dk; a.dv = p->dv;
+  a.B = p->B; a.N = p->N; a.H = p->H; a.Hkv = p->Hkv; a.D = p->D; a.G = p->G;
+  a.r = p->H / p->Hkv;
+  a.shift = resolved_shift(p);
+  a.shifted_from = shifted_from(p->shift_rule, p->H, a.shift);
+  a.split = (p->wrap_variant == S2ATTN_WRAP_SPLIT && a.shift > 0) ? p->G - a.shift : p->G;
+  a.mixed = kv_heads_mixed(p->H, p->Hkv, a.shifted_from) ? 1 : 0;
+  a.scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->D);
+  a.scale_log2 = a.scale * 1.4426950408889634f;
+  return a;
+}
+
+s2attn_params basic_params(const void* q, const void* k, const void* v, void* o, float* lse,
+                           int B, int N, int H, int Hkv, int D, int G, int dtype) {
+  s2attn_params p;
+  std::memset(&p, 0, sizeof(p));
+  p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse;
+  p.B = B; p.N = N; p.H = H; p.Hkv = Hkv; p.D = D; p.G = G;
+  p.dtype = dtype;
+  p.shift = -1;
+  p.shift_rule = S2ATTN_SHIFT_SECOND_HALF;
+  p.wrap_variant = S2ATTN_WRAP_JOINT;
+  p.scale = 0.f;
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int s2attn_check_args(const s2attn_params* p, int backward) { return check_common(p, backward); }
+
+size_t s2attn_bwd_workspace_bytes(int B, int N, int H, int Hkv, int D, int G, int dtype) {
+  (void)G; (void)dtype;
+  if (B <= 0 || N <= 0 || H <= 0 || Hkv <= 0 || D <= 0 || H % Hkv != 0) return 0;
+  // sized for the default rule; the other rules never mix classes inside a kv head
+  const bool mixed = kv_heads_mixed(H, Hkv, H / 2);
+  return workspace_bytes_for(B, N, H, Hkv, D, mixed);
+}
+
+int s2attn_fwd_ex(const s2attn_params* p, void* stream) {
+  int rc = check_common(p, 0);
+  if (rc != S2ATTN_OK) return rc;
+  rc = check_device();
+  if (rc != S2ATTN_OK) return rc;
+  s2::KArgs a = make_kargs(p);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  rc = p->dtype == S2ATTN_F32 ? s2::launch_fwd_f32(a, st) : s2::launch_fwd_bf16(a, st);
+  return rc == 0 ? S2ATTN_OK : S2ATTN_ERR_LAUNCH;
+}
+
+int s2attn_bwd_ex(const s2attn_params* p, void* stream) {
+  int rc = check_common(p, 1);
+  if (rc != S2ATTN_OK) return rc;
+  rc = check_device();
+  if (rc != S2ATTN_OK) return rc;
+  s2::KArgs a = make_kargs(p);
+  a.delta = static_cast<float*>(p->workspace);
+  if (a.mixed)
+    a.dkv_partial = reinterpret_cast<float*>(static_cast<char*>(p->workspace) + delta_bytes(p->B, p->N, p->H));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (s2::launch_delta(a, p->dtype, st) != 0) return S2ATTN_ERR_LAUNCH;
+  rc = p->dtype == S2ATTN_F32 ? s2::launch_bwd_f32(a, st) : s2::launch_bwd_bf16(a, st);
+  if (rc != 0) return S2ATTN_ERR_LAUNCH;
+  if (a.mixed && s2::launch_combine_partials(a, p->dtype, st) != 0) return S2ATTN_ERR_LAUNCH;
+  return S2ATTN_OK;
+}
+
+int s2attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+               int B, int N, int H, int Hkv, int D, int G, void* stream) {
+  s2attn_params p = basic_params(q, k, v, o, lse, B, N, H, Hkv, D, G, S2ATTN_BF16);
+  return s2attn_fwd_ex(&p, stream);
+}
+
+int s2attn_fwd_f32(const float* q, const float* k, const float* v, float* o, float* lse,
+                   int B, int N, int H, int Hkv, int D, int G, void* stream) {
+  s2attn_params p = basic_params(q, k, v, o, lse, B, N, H, Hkv, D, G, S2ATTN_F32);
+  return s2attn_fwd_ex(&p, stream);
+}
+
+int s2attn_bwd(const void* q, const void* k, const void* v, const void* o,
+               const void* dout, const float* lse, void* dq, void* dk, void* dv,
+               void* workspace, size_t workspace_bytes,
+               int B, int N, int H, int Hkv, int D, int G, void* stream) {
+  s2attn_params p = basic_params(q, k, v, const_cast<void*>(o), const_cast<float*>(lse),
+                                 B, N, H, Hkv, D, G, S2ATTN_BF16);
+  p.dout = dout; p.dq = dq; p.dk = dk; p.dv = dv;
+  p.workspace = workspace; p.workspace_bytes = workspace_bytes;
+  return s2attn_bwd_ex(&p, stream);
+}
+
+int s2attn_bwd_f32(const float* q, const float* k, const float* v, const float* o,
+                   const float* dout, const float* lse, float* dq, float* dk, float* dv,
+                   void* workspace, size_t workspace_bytes,
+                   int B, int N, int H, int Hkv, int D, int G, void* stream) {
+  s2attn_params p = basic_params(q, k, v, const_cast<float*>(o), const_cast<float*>(lse),
+                                 B, N, H, Hkv, D, G, S2ATTN_F32);
+  p.dout = dout; p.dq = dq; p.dk = dk; p.dv = dv;
+  p.workspace = workspace; p.workspace_bytes = workspace_bytes;
+  return s2attn_bwd_ex(&p, stream);
+}
+
+const char* s2attn_strerror(int code) {
+  switch (code) {
+    case S2ATTN_OK: return "ok";
+    case S2ATTN_ERR_NULL: return "a required pointer is NULL";
+    case S2ATTN_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned (workspace: 256-byte)";
+    case S2ATTN_ERR_DIM: return "B, N, H, Hkv, D and G must be positive";
+    case S2ATTN_ERR_GROUP: return "need N % G == 0, G even and 0 <= shift < G";
+    case S2ATTN_ERR_HEADS: return "need H even and H % Hkv == 0";
+    case S2ATTN_ERR_HEADDIM: return "unsupported head dimension (fp32: 64 or 128; bf16: 128)";
+    case S2ATTN_ERR_TILE: return "bf16 path needs G and shift to be multiples of 128";
+    case S2ATTN_ERR_WORKSPACE: return "backward workspace missing or smaller than s2attn_bwd_workspace_bytes";
+    case S2ATTN_ERR_DTYPE: return "unknown dtype, shift rule or wrap variant";
+    case S2ATTN_ERR_DEVICE: return "current device is not gfx950 (MI355X)";
+    case S2ATTN_ERR_LAUNCH: return "HIP kernel launch failed";
+    case S2ATTN_ERR_TOO_LARGE: return "problem too large for the launch grid or index arithmetic";
+    default: return "unknown s2attn error code";
+  }
+}
+
+double s2attn_effective_flops(int B, int N, int H, int D, int G, int pass) {
+  const double pairs = (double)B * H * N * (G + 1) / 2.0;
+  const double per_pair = pass == 0 ? 4.0 : (pass == 1 ? 10.0 : 14.0);
+  return pairs * D * per_pair;
+}
+
+}  // extern "C"

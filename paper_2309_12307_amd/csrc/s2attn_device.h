@@ -1,0 +1,43 @@
+// Shared between the host API and the kernels: the launch argument block and the
+// shift/group index map of S2-Attn (LongLoRA Section 3.2, Algorithm 1).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace s2 {
+
+struct KArgs {
+  const void* q; const void* k; const void* v;
+  void* o; float* lse;                       // forward outputs / backward inputs
+  const void* dout;
+  void* dq; void* dk; void* dv;
+  float* delta;                              // (B,H,N) fp32
+  float* dkv_partial;                        // fp32 [2 tensors][2 classes][B,N,Hkv,D] or null
+  int B, N, H, Hkv, D, G;
+  int r;                                     // H / Hkv
+  int shift;                                 // tokens, 0 <= shift < G
+  int shifted_from;                          // heads >= shifted_from use the shifted partition
+  int split;                                 // Variant 2: rows [0,split) | [split,G) of the wrap group; G = off
+  int mixed;                                 // some kv head serves both head classes
+  float scale;                               // softmax scale
+  float scale_log2;                          // scale * log2(e)
+};
+
+// Rolled position p of a head with shift s holds token (p + s) mod N
+// (roll(x, -s) in Algorithm 1's first key line; both p and s are < N).
+__device__ __forceinline__ int token_of(int p, int s, int N) {
+  int t = p + s;
+  return t >= N ? t - N : t;
+}
+
+__device__ __forceinline__ int shift_of_head(const KArgs& a, int h) {
+  return h >= a.shifted_from ? a.shift : 0;
+}
+
+// First visible key index for query row i of group g (0 except under Variant 2
+// in the wrap-around group of a shifted head, Appendix B.3).
+__device__ __forceinline__ int split_of_group(const KArgs& a, int g, int s) {
+  return (s > 0 && g == a.N / a.G - 1) ? a.split : a.G;   // a.split == G means "no split"
+}
+
+}  // namespace s2

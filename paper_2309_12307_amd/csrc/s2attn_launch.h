@@ -1,0 +1,19 @@
+// Internal launch entry points, one per kernel family.  Each returns 0 or -1
+// (HIP launch error) and only enqueues work on the given stream.
+#pragma once
+#include "s2attn_device.h"
+
+namespace s2 {
+
+int launch_fwd_f32(const KArgs& a, hipStream_t st);
+int launch_bwd_f32(const KArgs& a, hipStream_t st);   // dK/dV + dQ (delta must be ready)
+
+int launch_fwd_bf16(const KArgs& a, hipStream_t st);
+int launch_bwd_bf16(const KArgs& a, hipStream_t st);  // dK/dV + dQ (delta must be ready)
+
+// delta[b,h,t] = sum_d dout[b,t,h,d] * o[b,t,h,d], fp32
+int launch_delta(const KArgs& a, int dtype, hipStream_t st);
+// dk = partial[class 0] + partial[class 1] (same for dv), cast to the output type
+int launch_combine_partials(const KArgs& a, int dtype, hipStream_t st);
+
+}  // namespace s2

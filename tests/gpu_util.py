@@ -1,0 +1,57 @@
+"""Helpers for the GPU parity tests: move seeded inputs to the device, run the HIP
+path through the C ABI (via the ctypes binding) and bring the results back."""
+import numpy as np
+import torch
+
+from paper_2309_12307_amd import binding
+
+
+def to_dev(x: np.ndarray, bits: np.ndarray | None = None):
+    if bits is not None:
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.float().cpu().numpy()
+
+
+def run_hip(inp: dict, G: int, dtype: str, backward=True, **ex):
+    """inp: dict from inputs.make_inputs.  Returns dict of numpy float32 arrays
+    o, lse, dq, dk, dv (gradients only when backward).  Extra keyword arguments
+    (shift, shift_rule, wrap_variant, scale) go through the *_ex entry points."""
+    bf = dtype == "bf16"
+    q = to_dev(inp["q"], inp.get("q_bits") if bf else None)
+    k = to_dev(inp["k"], inp.get("k_bits") if bf else None)
+    v = to_dev(inp["v"], inp.get("v_bits") if bf else None)
+    do = to_dev(inp["do"], inp.get("do_bits") if bf else None)
+    B, N, H, D = q.shape
+    Hkv = k.shape[2]
+    o = torch.full_like(q, float("nan"))
+    lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    if ex:
+        p = binding.make_params(q, k, v, o, lse, G, **ex)
+        binding.s2attn_fwd_ex(p)
+    else:
+        binding.s2attn_fwd(q, k, v, o, lse, G)
+    out = {}
+    if backward:
+        dq = torch.full_like(q, float("nan"))
+        dk = torch.full_like(k, float("nan"))
+        dv = torch.full_like(v, float("nan"))
+        nbytes = binding.bwd_workspace_bytes(B, N, H, Hkv, D, G, binding.BF16 if bf else binding.F32)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        if ex:
+            p = binding.make_params(q, k, v, o, lse, G, dout=do, dq=dq, dk=dk, dv=dv, workspace=ws, **ex)
+            binding.s2attn_bwd_ex(p)
+        else:
+            binding.s2attn_bwd(q, k, v, o, do, lse, dq, dk, dv, ws, G)
+        torch.cuda.synchronize()
+        out.update(dq=to_np(dq), dk=to_np(dk), dv=to_np(dv))
+    torch.cuda.synchronize()
+    out.update(o=to_np(o), lse=to_np(lse))
+    return out
+
+
+def max_abs(a, b):
+    return float(np.max(np.abs(np.asarray(a, dtype=np.float64) - np.asarray(b, dtype=np.float64))))

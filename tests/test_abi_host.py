@@ -1,0 +1,107 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and the pure-host argument validator returns the
+documented codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2309_12307_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "s2attn.h")).read()
+    return sorted(set(re.findall(r"S2ATTN_API\s+[\w\s\*]+?\b(s2attn_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    L = binding.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_strerror_and_flops():
+    assert binding.strerror(0) == "ok"
+    for code in range(-12, 0):
+        assert "error code" not in binding.strerror(code)
+    assert "error code" in binding.strerror(-99)
+    # C3 of the benchmark: 7.698 effective TFLOP forward+backward
+    assert abs(binding.effective_flops(1, 32768, 32, 128, 8192, 2) / 1e12 - 7.698) < 1e-3
+    assert binding.effective_flops(1, 32768, 32, 128, 8192, 0) * 3.5 == pytest.approx(
+        binding.effective_flops(1, 32768, 32, 128, 8192, 2))
+
+
+def params(**kw):
+    d = dict(B=1, N=1024, H=4, Hkv=4, D=128, G=256, dtype=binding.BF16)
+    d.update(kw)
+    p = binding.S2AttnParams()
+    fake = 0x10000
+    for f in ("q", "k", "v", "o", "lse", "dout", "dq", "dk", "dv", "workspace"):
+        setattr(p, f, kw.get(f, fake))
+    p.workspace_bytes = kw.get("workspace_bytes", 1 << 40)
+    for f in ("B", "N", "H", "Hkv", "D", "G", "dtype"):
+        setattr(p, f, d[f])
+    p.shift = kw.get("shift", -1)
+    p.shift_rule = kw.get("shift_rule", 0)
+    p.wrap_variant = kw.get("wrap_variant", 0)
+    p.scale = 0.0
+    return p
+
+
+def test_validator_accepts_benchmark_shapes():
+    from paper_2309_12307_amd.inputs import CONFIGS
+    for c in CONFIGS.values():
+        p = params(B=c.B, N=c.N, H=c.H, Hkv=c.Hkv, D=c.D, G=c.G,
+                   dtype=binding.BF16 if c.dtype == "bf16" else binding.F32)
+        assert binding.check_args(p, True) == 0, c.name
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(q=0), -1),
+    (dict(dv=0), -1),
+    (dict(k=0x10008), -2),
+    (dict(workspace=0x10010), -2),
+    (dict(N=0), -3),
+    (dict(N=1000), -4),                       # N % G != 0
+    (dict(G=255, N=1020, dtype=1, D=64), -4),  # odd G
+    (dict(shift=256), -4),
+    (dict(H=3, Hkv=3), -5),
+    (dict(H=4, Hkv=3), -5),
+    (dict(D=96), -6),
+    (dict(D=64), -6),                         # bf16 supports D = 128 only
+    (dict(G=64, N=1024), -7),
+    (dict(workspace_bytes=16), -8),
+    (dict(workspace=0), -8),
+    (dict(dtype=5), -9),
+    (dict(shift_rule=7), -9),
+    (dict(wrap_variant=1), -9),
+    (dict(B=40000), -12),
+])
+def test_validator_codes(kw, code):
+    assert binding.check_args(params(**kw), True) == code
+
+
+def test_forward_check_ignores_backward_fields():
+    p = params(dout=0, dq=0, dk=0, dv=0, workspace=0, workspace_bytes=0)
+    assert binding.check_args(p, False) == 0
+    assert binding.check_args(p, True) == -1
+
+
+def test_workspace_size():
+    # delta only: B*H*N floats rounded to 256 bytes
+    assert binding.bwd_workspace_bytes(1, 32768, 32, 32, 128, 8192) == 32 * 32768 * 4
+    # MQA: one kv head serves shifted and unshifted heads -> fp32 partials too
+    w = binding.bwd_workspace_bytes(1, 256, 4, 1, 64, 64, binding.F32)
+    assert w == 4 * 256 * 4 + 4 * 256 * 64 * 4
+
+
+def test_missing_library_is_an_error(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.lib()

@@ -1,0 +1,107 @@
+"""fp32 mode: HIP path vs the CPU oracle, element by element (max-abs <= 1e-4 on
+o, lse, dq, dk, dv), through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import s2attn_oracle as orc
+from paper_2309_12307_amd import inputs
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+def compare(out, ref, tol=TOL):
+    o, lse, dq, dk, dv = ref
+    errs = {
+        "o": np.abs(out["o"] - o).max(), "lse": np.abs(out["lse"] - lse).max(),
+        "dq": np.abs(out["dq"] - dq).max(), "dk": np.abs(out["dk"] - dk).max(),
+        "dv": np.abs(out["dv"] - dv).max(),
+    }
+    for name, e in errs.items():
+        assert np.isfinite(e) and e <= tol, (name, errs)
+    return errs
+
+
+def test_config_c1():
+    from gpu_util import run_hip
+    cfg = inputs.CONFIGS["C1"]
+    inp = inputs.make_config_inputs(cfg)
+    out = run_hip(inp, cfg.G, "f32")
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], cfg.G)
+    compare(out, ref)
+
+
+# (B, N, H, Hkv, D, G): several tiles, ragged tails (G not a multiple of 64), GQA,
+# MQA with a kv head shared by shifted and unshifted heads, D = 128, one group
+SHAPES = [
+    (2, 384, 4, 4, 64, 128),
+    (1, 400, 4, 2, 64, 200),
+    (1, 300, 6, 3, 64, 100),
+    (1, 288, 4, 1, 64, 96),
+    (2, 256, 2, 2, 128, 128),
+    (1, 140, 2, 1, 128, 70),
+    (1, 192, 2, 2, 64, 192),
+    (1, 24, 2, 2, 64, 6),
+    (1, 4, 2, 2, 64, 2),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_shapes(shape):
+    from gpu_util import run_hip
+    B, N, H, Hkv, D, G = shape
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=sum(shape), dtype="f32")
+    out = run_hip(inp, G, "f32")
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G)
+    compare(out, ref)
+
+
+def test_full_causal_attention_mode():
+    """G = N with no shifted head degenerates to plain causal attention."""
+    from gpu_util import run_hip
+    from paper_2309_12307_amd import binding
+    B, N, H, Hkv, D = 1, 320, 2, 2, 64
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=77, dtype="f32")
+    out = run_hip(inp, N, "f32", shift_rule=binding.SHIFT_NONE)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], N, shift_heads="none")
+    compare(out, ref)
+
+
+@pytest.mark.parametrize("rule,name", [(1, "none"), (2, "all")])
+def test_shift_rules(rule, name):
+    from gpu_util import run_hip
+    B, N, H, Hkv, D, G = 1, 384, 4, 2, 64, 128
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=78 + rule, dtype="f32")
+    out = run_hip(inp, G, "f32", shift_rule=rule)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, shift_heads=name)
+    compare(out, ref)
+
+
+def test_custom_shift_and_scale():
+    from gpu_util import run_hip
+    B, N, H, Hkv, D, G = 1, 384, 4, 4, 64, 128
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=80, dtype="f32")
+    out = run_hip(inp, G, "f32", shift=40, scale=0.2)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, shift=40, scale=0.2)
+    compare(out, ref)
+
+
+@pytest.mark.parametrize("shape", [(1, 384, 4, 4, 64, 128), (1, 400, 4, 2, 64, 200), (1, 288, 4, 1, 64, 96)])
+def test_variant2_split_wrap_group(shape):
+    from gpu_util import run_hip
+    from paper_2309_12307_amd import binding
+    B, N, H, Hkv, D, G = shape
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=81, dtype="f32")
+    out = run_hip(inp, G, "f32", wrap_variant=binding.WRAP_SPLIT)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, variant2=True)
+    compare(out, ref)
+
+
+def test_outputs_are_deterministic():
+    from gpu_util import run_hip
+    cfg = inputs.CONFIGS["C1"]
+    inp = inputs.make_config_inputs(cfg)
+    a = run_hip(inp, cfg.G, "f32")
+    b = run_hip(inp, cfg.G, "f32")
+    for name in a:
+        assert np.array_equal(a[name], b[name]), name
