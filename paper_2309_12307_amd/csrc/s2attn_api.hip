@@ -59,7 +59,7 @@ int check_common(const s2attn_params* p, int backward) {
     if (p->D != 64 && p->D != 128) return S2ATTN_ERR_HEADDIM;
   } else {
     if (p->D != 128) return S2ATTN_ERR_HEADDIM;
-    if (p->G % 128 != 0 || shift % 128 != 0) return S2ATTN_ERR_TILE;
+    if (p->G % 128 != 0 || shift % 64 != 0) return S2ATTN_ERR_TILE;
   }
   // grid z carries batch * heads (* 2 classes); element offsets are 64-bit
   if ((long long)p->B * p->H * 2 > 65535 || (long long)p->N / p->G > 65535) return S2ATTN_ERR_TOO_LARGE;
@@ -215,7 +215,7 @@ const char* s2attn_strerror(int code) {
     case S2ATTN_ERR_GROUP: return "need N % G == 0, G even and 0 <= shift < G";
     case S2ATTN_ERR_HEADS: return "need H even and H % Hkv == 0";
     case S2ATTN_ERR_HEADDIM: return "unsupported head dimension (fp32: 64 or 128; bf16: 128)";
-    case S2ATTN_ERR_TILE: return "bf16 path needs G and shift to be multiples of 128";
+    case S2ATTN_ERR_TILE: return "bf16 path needs G to be a multiple of 128 and shift a multiple of 64";
     case S2ATTN_ERR_WORKSPACE: return "backward workspace missing or smaller than s2attn_bwd_workspace_bytes";
     case S2ATTN_ERR_DTYPE: return "unknown dtype, shift rule or wrap variant";
     case S2ATTN_ERR_DEVICE: return "current device is not gfx950 (MI355X)";

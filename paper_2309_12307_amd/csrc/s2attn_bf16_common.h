@@ -1,0 +1,109 @@
+// Building blocks of the bf16 MFMA kernels (gfx950 only): vector types, the
+// swizzled LDS tile layout, MFMA operand fragment loads and small wave-level
+// helpers.
+//
+// MFMA v_mfma_f32_32x32x16_bf16 operand layout (lane l, g = l / 32):
+//   A (32 x 16):  row  l % 32, contraction elements 8g .. 8g+7
+//   B (16 x 32):  col  l % 32, contraction elements 8g .. 8g+7
+//   C (32 x 32):  col  l % 32, register v holds row 8*(v/4) + 4g + (v%4)
+// Only the pairing of A and B contraction slots matters, so an accumulator tile can
+// be fed back as a B operand without any cross-lane movement when the other operand
+// is loaded with the matching row permutation: B slot e of k-step t (16 rows) takes
+// accumulator register 8t + e, i.e. row 16t + 8*(e/4) + 4g + (e%4).
+//
+// LDS tiles hold 128 bf16 (256 bytes) per row, unpadded, with the sixteen 16-byte
+// chunks of a row XOR-permuted by a function of the row.  The permutation makes both
+// access patterns bank-conflict free: row-major 16-byte reads by 16 consecutive rows
+// and transposing ds_read_b64_tr_b16 reads of 4 consecutive rows x 64 bytes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace s2 {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define S2_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+constexpr int kRowBytes = 256;          // one tile row: 128 bf16
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+// Byte offset of 16-byte chunk `chunk` (0..15) of row `row` inside a tile.
+__device__ __forceinline__ int tile_off(int row, int chunk) {
+  return row * kRowBytes + ((chunk ^ swz(row)) << 4);
+}
+
+// Row-major operand fragment: elements [8*chunk, 8*chunk+8) of `row`.
+__device__ __forceinline__ bf16x8 frag_rm(const char* tile, int row, int chunk) {
+  return *reinterpret_cast<const bf16x8*>(tile + tile_off(row, chunk));
+}
+
+// Transposed operand fragment: the operand row index runs along the tile's columns
+// (32 columns starting at 32*cb) and the contraction index along 16 tile rows starting
+// at krow0, in the accumulator-feedback order described above.  Two transposing
+// 64-bit LDS reads: within each block of 16 lanes, lane L points at 4 elements of tile
+// row (L / 4) and receives one column of the 4 rows.
+__device__ __forceinline__ bf16x8 frag_tr(const char* tile, int krow0, int cb, int lane) {
+  const int g = lane >> 5, L = lane & 15, half = lane & 16;
+  const int row = krow0 + 4 * g + (L >> 2);
+  const int col = 32 * cb + half + 4 * (L & 3);
+  const int chunk = col >> 3, within = (col & 7) * 2;
+  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+      S2_LDS(bf16x4, tile + row * kRowBytes + ((chunk ^ swz(row)) << 4) + within));
+  const int row2 = row + 8;
+  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+      S2_LDS(bf16x4, tile + row2 * kRowBytes + ((chunk ^ swz(row2)) << 4) + within));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Value of the same register in lane (l ^ 32).
+__device__ __forceinline__ float other_half(float x) {
+  const uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  // lanes < 32 receive the partner in r[1], lanes >= 32 in r[0]
+  return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+
+__device__ __forceinline__ float max_halves(float x) {
+  const uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ __forceinline__ float sum_halves(float x) {
+  const uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3,
+                                        float a4, float a5, float a6, float a7) {
+  bf16x8 r;
+  r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
+  r[4] = (__bf16)a4; r[5] = (__bf16)a5; r[6] = (__bf16)a6; r[7] = (__bf16)a7;
+  return r;
+}
+
+__device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) {
+  bf16x4 r;
+  r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
+  return r;
+}
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) z[i] = 0.f;
+  return z;
+}
+
+}  // namespace s2
