@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the S2-Attn hot path (forward + backward) on one MI355X.
+
+One step = one forward and one backward pass of a whole S2-Attn layer over one batch of
+synthetic inputs (iid N(0,1), rounded to bf16) that are resident in HBM before the timed
+region.  The default workload is the Llama2-7B-shaped layer at N = 32768, G = 8192.
+Prints ONE JSON line: effective TFLOP/s (only in-group causal pairs are counted:
+14*D FLOP per (query, key) pair for forward + backward), the roofline of the dominant
+kernel measured with HIP events on the launch stream, and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/),
+# keyed by workload then kernel; None until measured.
+MEASURED_TRAFFIC = {}
+
+
+class HipEvents:
+    """Raw HIP events through the runtime torch already loaded, so they can be
+    recorded on the stream the library launches on."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self) -> int:
+        e = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(e))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        return e.value
+
+    def record(self, ev: int, stream: int) -> None:
+        rc = self.hip.hipEventRecord(ev, stream)
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed: {rc}")
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def destroy(self, ev: int) -> None:
+        self.hip.hipEventDestroy(ev)
+
+
+def cpu_baseline(cfg, inp, budget_s=20.0):
+    """The oracle as it stands, on a bounded sample: whole (kv head, group) slices of the
+    workload, forward + backward in fp32, until about `budget_s` seconds are spent."""
+    from oracle import s2attn_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    r = cfg.H // cfg.Hkv
+    pairs_per_slice = r * cfg.G * (cfg.G + 1) // 2
+    picks = [(0, 0), (cfg.Hkv - 1, cfg.N // cfg.G - 1), (cfg.Hkv - 1, 0), (0, cfg.N // cfg.G - 1)]
+    done, t_total = 0, 0.0
+    for c, g in picks:
+        t0 = time.perf_counter()
+        orc.s2attn_group_slice(inp["q"], inp["k"], inp["v"], inp["do"], cfg.G, 0, c, g, dtype=np.float32)
+        t_total += time.perf_counter() - t0
+        done += 1
+        if t_total > budget_s:
+            break
+    flops = 14.0 * cfg.D * pairs_per_slice * done
+    return {
+        "value": flops / t_total / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"{done} of {cfg.B * cfg.Hkv * (cfg.N // cfg.G)} (kv head, group) slices of {cfg.name}, "
+                  f"fwd+bwd in fp32 numpy, {t_total:.1f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C3", help="C2 | C3 | C4 | C5 (bf16 configurations)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU S2-Attn kernels only: this build has no multi-GPU path "
+              "(--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2309_12307_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU fallback)", file=sys.stderr)
+        sys.exit(2)
+    cfg = inputs.CONFIGS[args.workload]
+    if cfg.dtype != "bf16":
+        raise SystemExit("bench workloads are the bf16 configurations")
+    binding.lib()   # fail loudly before any work if the library is missing
+
+    inp = inputs.make_config_inputs(cfg)
+
+    def dev(name):
+        return torch.from_numpy(inp[name + "_bits"].view(np.int16)).cuda().view(torch.bfloat16)
+
+    q, k, v, do = dev("q"), dev("k"), dev("v"), dev("do")
+    o = torch.empty_like(q)
+    lse = torch.empty((cfg.B, cfg.H, cfg.N), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(binding.bwd_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.Hkv, cfg.D, cfg.G), dtype=torch.uint8,
+                     device="cuda")
+    p_bwd = binding.make_params(q, k, v, o, lse, cfg.G, dout=do, dq=dq, dk=dk, dv=dv, workspace=ws)
+    stream = torch.cuda.current_stream().cuda_stream
+    ev = HipEvents()
+
+    def step(marks=None):
+        if marks is not None:
+            ev.record(marks[0], stream)
+        binding.s2attn_fwd(q, k, v, o, lse, cfg.G, stream=stream)
+        if marks is not None:
+            binding.s2attn_bwd_ex_marked(p_bwd, marks[1:5], stream=stream)
+        else:
+            binding.s2attn_bwd_ex(p_bwd, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    marks = [[ev.create() for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(marks[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # per-kernel durations from the events of the timed region
+    names = ["fwd", "bwd_delta", "bwd_dkdv", "bwd_dq"]
+    dur = {n: 0.0 for n in names}
+    for m in marks:
+        for j, n in enumerate(names):
+            dur[n] += ev.elapsed_ms(m[j], m[j + 1])
+    for n in names:
+        dur[n] /= args.steps
+    for m in marks:
+        for e in m:
+            ev.destroy(e)
+
+    pairs = cfg.B * cfg.H * cfg.N * (cfg.G + 1) / 2.0
+    flops_total = binding.effective_flops(cfg.B, cfg.N, cfg.H, cfg.D, cfg.G, 2)
+    # algorithmic FLOPs per launch: forward 4D per pair; dK/dV kernel 8D (S, dP, dV, dK);
+    # dQ kernel 2D (its recomputation of S and dP is not credited)
+    alg = {"fwd": 4.0 * cfg.D * pairs, "bwd_dkdv": 8.0 * cfg.D * pairs, "bwd_dq": 2.0 * cfg.D * pairs}
+    kernels = {n: {"ms": dur[n], "algorithmic_tflops": alg[n] / dur[n] / 1e9 if n in alg else None} for n in names}
+    dom = max(alg, key=lambda n: dur[n])
+    achieved = alg[dom] / dur[dom] / 1e9
+    traffic = MEASURED_TRAFFIC.get(cfg.name, {}).get(dom)
+
+    value = flops_total / (ms_per_step * 1e-3) / 1e12
+    out = {
+        "metric": "S2-Attn fwd+bwd effective TFLOP/s (in-group causal FLOPs only)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: S2-Attn layer fwd+bwd, B={cfg.B} N={cfg.N} H={cfg.H} Hkv={cfg.Hkv} "
+                               f"D={cfg.D} G={cfg.G} shift={cfg.G // 2} on heads >= H/2",
+                   "effective_tflop_per_step": flops_total / 1e12},
+        "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, inp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -127,6 +127,12 @@ S2ATTN_API int s2attn_bwd_f32(const float* q, const float* k, const float* v, co
 S2ATTN_API int s2attn_fwd_ex(const s2attn_params* p, void* stream);
 S2ATTN_API int s2attn_bwd_ex(const s2attn_params* p, void* stream);
 
+/* Measurement aid: s2attn_bwd_ex that also records up to four caller-owned HIP events
+ * (hipEvent_t passed as void*, entries may be NULL) on `stream`: events[0] before the
+ * delta pre-pass, [1] after it, [2] after the dK/dV kernel, [3] after the dQ kernel
+ * (and the partial-sum pass, when present).  Same semantics and errors otherwise. */
+S2ATTN_API int s2attn_bwd_ex_marked(const s2attn_params* p, void* stream, void* const* events);
+
 /* Static, never-freed message for a return code. */
 S2ATTN_API const char* s2attn_strerror(int code);
 

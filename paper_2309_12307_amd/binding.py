@@ -20,7 +20,7 @@ WRAP_JOINT, WRAP_SPLIT = 0, 2
 EXPORTS = [
     "s2attn_check_args", "s2attn_bwd_workspace_bytes", "s2attn_fwd", "s2attn_bwd",
     "s2attn_fwd_f32", "s2attn_bwd_f32", "s2attn_fwd_ex", "s2attn_bwd_ex",
-    "s2attn_strerror", "s2attn_effective_flops",
+    "s2attn_strerror", "s2attn_effective_flops", "s2attn_bwd_ex_marked",
 ]
 
 
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.argtypes = [ctypes.POINTER(S2AttnParams), vp]
             f.restype = i
+        L.s2attn_bwd_ex_marked.argtypes = [ctypes.POINTER(S2AttnParams), vp, ctypes.POINTER(vp)]
+        L.s2attn_bwd_ex_marked.restype = i
         L.s2attn_strerror.argtypes = [i]
         L.s2attn_strerror.restype = ctypes.c_char_p
         L.s2attn_effective_flops.argtypes = [i] * 6
@@ -179,3 +181,9 @@ def s2attn_fwd_ex(p: S2AttnParams, stream=None) -> None:
 
 def s2attn_bwd_ex(p: S2AttnParams, stream=None) -> None:
     _check(lib().s2attn_bwd_ex(ctypes.byref(p), _stream(stream)))
+
+
+def s2attn_bwd_ex_marked(p: S2AttnParams, events, stream=None) -> None:
+    """events: sequence of four raw hipEvent_t handles (ints) or None entries."""
+    arr = (ctypes.c_void_p * 4)(*[e if e else None for e in events])
+    _check(lib().s2attn_bwd_ex_marked(ctypes.byref(p), _stream(stream), arr))

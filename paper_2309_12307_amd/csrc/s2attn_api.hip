@@ -155,7 +155,7 @@ int s2attn_fwd_ex(const s2attn_params* p, void* stream) {
   return rc == 0 ? S2ATTN_OK : S2ATTN_ERR_LAUNCH;
 }
 
-int s2attn_bwd_ex(const s2attn_params* p, void* stream) {
+static int run_bwd(const s2attn_params* p, void* stream, void* const* events) {
   int rc = check_common(p, 1);
   if (rc != S2ATTN_OK) return rc;
   rc = check_device();
@@ -165,11 +165,26 @@ int s2attn_bwd_ex(const s2attn_params* p, void* stream) {
   if (a.mixed)
     a.dkv_partial = reinterpret_cast<float*>(static_cast<char*>(p->workspace) + delta_bytes(p->B, p->N, p->H));
   hipStream_t st = static_cast<hipStream_t>(stream);
+  auto mark = [&](int i) {
+    if (events && events[i]) (void)hipEventRecord(static_cast<hipEvent_t>(events[i]), st);
+  };
+  mark(0);
   if (s2::launch_delta(a, p->dtype, st) != 0) return S2ATTN_ERR_LAUNCH;
-  rc = p->dtype == S2ATTN_F32 ? s2::launch_bwd_f32(a, st) : s2::launch_bwd_bf16(a, st);
+  mark(1);
+  rc = p->dtype == S2ATTN_F32 ? s2::launch_bwd_dkdv_f32(a, st) : s2::launch_bwd_dkdv_bf16(a, st);
+  if (rc != 0) return S2ATTN_ERR_LAUNCH;
+  mark(2);
+  rc = p->dtype == S2ATTN_F32 ? s2::launch_bwd_dq_f32(a, st) : s2::launch_bwd_dq_bf16(a, st);
   if (rc != 0) return S2ATTN_ERR_LAUNCH;
   if (a.mixed && s2::launch_combine_partials(a, p->dtype, st) != 0) return S2ATTN_ERR_LAUNCH;
+  mark(3);
   return S2ATTN_OK;
+}
+
+int s2attn_bwd_ex(const s2attn_params* p, void* stream) { return run_bwd(p, stream, nullptr); }
+
+int s2attn_bwd_ex_marked(const s2attn_params* p, void* stream, void* const* events) {
+  return run_bwd(p, stream, events);
 }
 
 int s2attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,

@@ -366,24 +366,23 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
 
 }  // namespace
 
-int launch_bwd_bf16(const KArgs& a, hipStream_t st) {
+int launch_bwd_dkdv_bf16(const KArgs& a, hipStream_t st) {
   const int NG = a.N / a.G;
-  {
-    const int ncls = a.mixed ? 2 : 1;
-    const int T = a.G / 128;
-    const int n_rest = a.B * a.Hkv * ncls * NG;
-    const int blocks = 8 * T * ((n_rest + 7) / 8);
-    hipLaunchKernelGGL(bwd_dkdv_bf16_kernel, dim3(blocks), dim3(256), 0, st, a, ncls, T, n_rest);
-    if (hipGetLastError() != hipSuccess) return -1;
-  }
-  {
-    const int T = a.G / 128;
-    const int n_rest = a.B * a.Hkv * NG;
-    const int blocks = 8 * T * a.r * ((n_rest + 7) / 8);
-    hipLaunchKernelGGL(bwd_dq_bf16_kernel, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
-    if (hipGetLastError() != hipSuccess) return -1;
-  }
-  return 0;
+  const int ncls = a.mixed ? 2 : 1;
+  const int T = a.G / 128;
+  const int n_rest = a.B * a.Hkv * ncls * NG;
+  const int blocks = 8 * T * ((n_rest + 7) / 8);
+  hipLaunchKernelGGL(bwd_dkdv_bf16_kernel, dim3(blocks), dim3(256), 0, st, a, ncls, T, n_rest);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_bwd_dq_bf16(const KArgs& a, hipStream_t st) {
+  const int NG = a.N / a.G;
+  const int T = a.G / 128;
+  const int n_rest = a.B * a.Hkv * NG;
+  const int blocks = 8 * T * a.r * ((n_rest + 7) / 8);
+  hipLaunchKernelGGL(bwd_dq_bf16_kernel, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 }  // namespace s2

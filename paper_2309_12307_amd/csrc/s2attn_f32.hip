@@ -407,11 +407,15 @@ int launch_fwd_t(const KArgs& a, hipStream_t st) {
 }
 
 template <int D>
-int launch_bwd_t(const KArgs& a, hipStream_t st) {
+int launch_dkdv_t(const KArgs& a, hipStream_t st) {
   const int ncls = a.mixed ? 2 : 1;
   dim3 g1((a.G + 63) / 64, a.N / a.G, a.B * a.Hkv * ncls);
   hipLaunchKernelGGL(bwd_dkdv_f32_kernel<D>, g1, dim3(kThreads), 0, st, a, ncls);
-  if (hipGetLastError() != hipSuccess) return -1;
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+template <int D>
+int launch_dq_t(const KArgs& a, hipStream_t st) {
   dim3 g2((a.G + 31) / 32, a.N / a.G, a.B * a.H);
   hipLaunchKernelGGL(bwd_dq_f32_kernel<D>, g2, dim3(kThreads), 0, st, a);
   return hipGetLastError() == hipSuccess ? 0 : -1;
@@ -423,8 +427,12 @@ int launch_fwd_f32(const KArgs& a, hipStream_t st) {
   return a.D == 64 ? launch_fwd_t<64>(a, st) : launch_fwd_t<128>(a, st);
 }
 
-int launch_bwd_f32(const KArgs& a, hipStream_t st) {
-  return a.D == 64 ? launch_bwd_t<64>(a, st) : launch_bwd_t<128>(a, st);
+int launch_bwd_dkdv_f32(const KArgs& a, hipStream_t st) {
+  return a.D == 64 ? launch_dkdv_t<64>(a, st) : launch_dkdv_t<128>(a, st);
+}
+
+int launch_bwd_dq_f32(const KArgs& a, hipStream_t st) {
+  return a.D == 64 ? launch_dq_t<64>(a, st) : launch_dq_t<128>(a, st);
 }
 
 }  // namespace s2
