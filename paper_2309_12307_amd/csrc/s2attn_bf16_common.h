@@ -61,6 +61,22 @@ __device__ __forceinline__ bf16x8 frag_tr(const char* tile, int krow0, int cb, i
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// Direct global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane i of
+// the wave fetches the 16 bytes at its own global address `g`, and they land at LDS byte
+// address lds_base + 16*i, where lds_base must be wave-uniform.  Issued as inline
+// assembly so that the compiler does not fence unrelated LDS reads behind it; the
+// caller waits with s_waitcnt vmcnt(0) and a barrier before the data is read.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(g) : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)S2_LDS(const char, p));
+}
+
+__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // Value of the same register in lane (l ^ 32).
 __device__ __forceinline__ float other_half(float x) {
   const uint32_t u = __float_as_uint(x);
