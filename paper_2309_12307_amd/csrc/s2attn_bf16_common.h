@@ -71,6 +71,12 @@ __device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
                :: "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(g) : "memory", "m0");
 }
 
+// Same with 4 bytes per lane (global_load_lds_dword): lane i lands at lds_base + 4*i.
+__device__ __forceinline__ void dma4(const void* g, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(g) : "memory", "m0");
+}
+
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)S2_LDS(const char, p));
 }
@@ -113,6 +119,19 @@ __device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) 
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Scheduling hint for the region since the last sched_barrier: N times
+// {1 MFMA, up to DS LDS reads, up to VA VALU/transcendental instructions}, so that the
+// vector work of one block is issued in the shadow of another block's matrix work.
+template <int N, int DS, int VA>
+__device__ __forceinline__ void interleave_mfma() {
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if (DS > 0) __builtin_amdgcn_sched_group_barrier(0x100, DS, 0);
+    if (VA > 0) __builtin_amdgcn_sched_group_barrier(0x402, VA, 0);
+  }
 }
 
 __device__ __forceinline__ f32x16 zero16() {
