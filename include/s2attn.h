@@ -98,7 +98,7 @@ typedef struct s2attn_params {
 S2ATTN_API int s2attn_check_args(const s2attn_params* p, int backward);
 
 /* Bytes of device workspace the backward needs: the fp32 row term
- * delta[b,h,t] = sum_d dout*o, plus fp32 partial dk/dv when a kv head serves both
+ * delta[b,h,t] = sum_d dout*o and a base-2 copy of lse, plus fp32 partial dk/dv when a kv head serves both
  * shifted and unshifted query heads (odd Hkv under the second-half rule). */
 S2ATTN_API size_t s2attn_bwd_workspace_bytes(int B, int N, int H, int Hkv, int D, int G, int dtype);
 

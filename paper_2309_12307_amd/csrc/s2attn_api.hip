@@ -40,7 +40,7 @@ bool kv_heads_mixed(int H, int Hkv, int from) {
 size_t delta_bytes(int B, int N, int H) { return round_up((size_t)B * H * N * sizeof(float), kAlign); }
 
 size_t workspace_bytes_for(int B, int N, int H, int Hkv, int D, bool mixed) {
-  size_t w = delta_bytes(B, N, H);
+  size_t w = 2 * delta_bytes(B, N, H);   // delta and lse * log2(e)
   if (mixed) w += round_up((size_t)4 * B * N * Hkv * D * sizeof(float), kAlign);
   return w;
 }
@@ -162,8 +162,9 @@ static int run_bwd(const s2attn_params* p, void* stream, void* const* events) {
   if (rc != S2ATTN_OK) return rc;
   s2::KArgs a = make_kargs(p);
   a.delta = static_cast<float*>(p->workspace);
+  a.lse2 = reinterpret_cast<float*>(static_cast<char*>(p->workspace) + delta_bytes(p->B, p->N, p->H));
   if (a.mixed)
-    a.dkv_partial = reinterpret_cast<float*>(static_cast<char*>(p->workspace) + delta_bytes(p->B, p->N, p->H));
+    a.dkv_partial = reinterpret_cast<float*>(static_cast<char*>(p->workspace) + 2 * delta_bytes(p->B, p->N, p->H));
   hipStream_t st = static_cast<hipStream_t>(stream);
   auto mark = [&](int i) {
     if (events && events[i]) (void)hipEventRecord(static_cast<hipEvent_t>(events[i]), st);

@@ -45,80 +45,152 @@ struct DkdvBlock {     // S and dP accumulators of one 32-query block
   f32x16 s, dp;
 };
 
-// S = Q K^T and dP = dO V^T for query block mb of the staged tile.
-__device__ __forceinline__ void dkdv_scores(DkdvBlock& blk, const char* Qs, const char* dOs, int mb,
-                                            const bf16x8 (&kf)[8], const bf16x8 (&vf)[8], int l32, int g32) {
-  blk.s = zero16();
-  blk.dp = zero16();
-  bf16x8 qa[4], da[4];
+struct DkdvTile {      // the staged query tile and per-lane constants
+  const char* Qs;
+  const char* dOs;
+  const float* lse2_s;
+  const float* delta_s;
+  float c2;
+  int lane, l32, g32;
+};
+
+// ---- fragment loads and MFMA groups, one "phase" = 8 MFMAs fed by 8 fragments
+// scores phase (block MB, k-steps 4H..4H+3): S += Q K^T, dP += dO V^T
+template <int MB, int H>
+__device__ __forceinline__ void load_sc(bf16x8 (&buf)[8], const DkdvTile& t) {
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      qa[i] = frag_rm(Qs, 32 * mb + l32, 2 * (4 * half + i) + g32);
-      da[i] = frag_rm(dOs, 32 * mb + l32, 2 * (4 * half + i) + g32);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      blk.s = mfma32(qa[i], kf[4 * half + i], blk.s);
-      blk.dp = mfma32(da[i], vf[4 * half + i], blk.dp);
-    }
+  for (int i = 0; i < 4; ++i) {
+    buf[i] = frag_rm(t.Qs, 32 * MB + t.l32, 2 * (4 * H + i) + t.g32);
+    buf[4 + i] = frag_rm(t.dOs, 32 * MB + t.l32, 2 * (4 * H + i) + t.g32);
   }
 }
+template <int H>
+__device__ __forceinline__ void mma_sc(const bf16x8 (&buf)[8], DkdvBlock& blk, const bf16x8 (&kf)[8],
+                                       const bf16x8 (&vf)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    blk.s = mfma32(buf[i], kf[4 * H + i], blk.s);
+    blk.dp = mfma32(buf[4 + i], vf[4 * H + i], blk.dp);
+  }
+}
+// accumulate phase (block MB, queries 16T..16T+15 of it): dV^T += dO^T P, dK^T += Q^T dS
+template <int MB, int T>
+__device__ __forceinline__ void load_acc(bf16x8 (&buf)[8], const DkdvTile& t) {
+#pragma unroll
+  for (int db = 0; db < 4; ++db) {
+    buf[db] = frag_tr(t.dOs, 32 * MB + 16 * T, db, t.lane);
+    buf[4 + db] = frag_tr(t.Qs, 32 * MB + 16 * T, db, t.lane);
+  }
+}
+template <int T>
+__device__ __forceinline__ void mma_acc(const bf16x8 (&buf)[8], const bf16x4 (&pq)[4], const bf16x4 (&dsq)[4],
+                                        f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4]) {
+  const bf16x8 pf = __builtin_shufflevector(pq[2 * T], pq[2 * T + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+  const bf16x8 dsf = __builtin_shufflevector(dsq[2 * T], dsq[2 * T + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+  for (int db = 0; db < 4; ++db) {
+    dv_acc[db] = mfma32(buf[db], pf, dv_acc[db]);
+    dk_acc[db] = mfma32(buf[4 + db], dsf, dk_acc[db]);
+  }
+}
+// P and dS for accumulator registers 4*QTR .. 4*QTR+3 of block MB (4 consecutive queries
+// per lane half), packed to bf16.  MASK: causal mask against this lane's key.
+template <int MB, int QTR, bool MASK>
+__device__ __forceinline__ void sm_quarter(const DkdvBlock& blk, const DkdvTile& t, bf16x4& pq, bf16x4& dsq,
+                                           int q_first = 0, int key = 0) {
+  const float4 l4 = *reinterpret_cast<const float4*>(t.lse2_s + 32 * MB + 8 * QTR + 4 * t.g32);
+  const float4 d4 = *reinterpret_cast<const float4*>(t.delta_s + 32 * MB + 8 * QTR + 4 * t.g32);
+  const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+  float p[4], ds[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int v = 4 * QTR + e;
+    float pv = __builtin_amdgcn_exp2f(fmaf(blk.s[v], t.c2, -ls[e]));
+    if (MASK) {
+      const int qrow = q_first + 8 * QTR + 4 * t.g32 + e;
+      if (key > qrow) pv = 0.f;
+    }
+    p[e] = pv;
+    ds[e] = pv * (blk.dp[v] - dl[e]);
+  }
+  pq = pack4(p[0], p[1], p[2], p[3]);
+  dsq = pack4(ds[0], ds[1], ds[2], ds[3]);
+}
 
-// P and dS of a block as packed bf16 B operands (two 16-query k-steps each).
+// Interior tile (all 4 x 32 queries visible to all 32 keys of the wave): 16 phases of
+// 8 MFMAs.  MFMA order per block n: scores(n), then accumulate(n) one block later, so
+// that the VALU work of block n (four quarters) always has independent MFMAs of blocks
+// n-1 / n+1 beside it; every phase also issues the LDS reads of the next phase into the
+// other fragment buffer.
+__device__ __forceinline__ void dkdv_interior_tile(const DkdvTile& t, const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
+                                                   f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4]) {
+#define S2_PHASE_END(DS, VA) interleave_mfma<8, DS, VA>(); __builtin_amdgcn_sched_barrier(0)
+  bf16x8 fa[8], fb[8];
+  DkdvBlock b0, b1;
+  bf16x4 pa[4], da[4], pb[4], db[4];
+  load_sc<0, 0>(fa, t);
+  __builtin_amdgcn_sched_barrier(0);
+  // 1-2: scores(0)
+  load_sc<0, 1>(fb, t); b0.s = zero16(); b0.dp = zero16(); mma_sc<0>(fa, b0, kf, vf); S2_PHASE_END(1, 0);
+  load_sc<1, 0>(fa, t); mma_sc<1>(fb, b0, kf, vf); S2_PHASE_END(1, 0);
+  // 3-4: scores(1) | softmax(0)
+  load_sc<1, 1>(fb, t); b1.s = zero16(); b1.dp = zero16(); mma_sc<0>(fa, b1, kf, vf);
+  sm_quarter<0, 0, false>(b0, t, pa[0], da[0]); sm_quarter<0, 1, false>(b0, t, pa[1], da[1]); S2_PHASE_END(2, 8);
+  load_acc<0, 0>(fa, t); mma_sc<1>(fb, b1, kf, vf);
+  sm_quarter<0, 2, false>(b0, t, pa[2], da[2]); sm_quarter<0, 3, false>(b0, t, pa[3], da[3]); S2_PHASE_END(3, 8);
+  // 5-6: accumulate(0) | softmax(1) first half
+  load_acc<0, 1>(fb, t); mma_acc<0>(fa, pa, da, dk_acc, dv_acc); sm_quarter<1, 0, false>(b1, t, pb[0], db[0]); S2_PHASE_END(3, 4);
+  load_sc<2, 0>(fa, t); mma_acc<1>(fb, pa, da, dk_acc, dv_acc); sm_quarter<1, 1, false>(b1, t, pb[1], db[1]); S2_PHASE_END(2, 4);
+  // 7-8: scores(2) | softmax(1) second half
+  load_sc<2, 1>(fb, t); b0.s = zero16(); b0.dp = zero16(); mma_sc<0>(fa, b0, kf, vf);
+  sm_quarter<1, 2, false>(b1, t, pb[2], db[2]); S2_PHASE_END(2, 4);
+  load_acc<1, 0>(fa, t); mma_sc<1>(fb, b0, kf, vf); sm_quarter<1, 3, false>(b1, t, pb[3], db[3]); S2_PHASE_END(3, 4);
+  // 9-10: accumulate(1) | softmax(2) first half
+  load_acc<1, 1>(fb, t); mma_acc<0>(fa, pb, db, dk_acc, dv_acc); sm_quarter<2, 0, false>(b0, t, pa[0], da[0]); S2_PHASE_END(3, 4);
+  load_sc<3, 0>(fa, t); mma_acc<1>(fb, pb, db, dk_acc, dv_acc); sm_quarter<2, 1, false>(b0, t, pa[1], da[1]); S2_PHASE_END(2, 4);
+  // 11-12: scores(3) | softmax(2) second half
+  load_sc<3, 1>(fb, t); b1.s = zero16(); b1.dp = zero16(); mma_sc<0>(fa, b1, kf, vf);
+  sm_quarter<2, 2, false>(b0, t, pa[2], da[2]); S2_PHASE_END(2, 4);
+  load_acc<2, 0>(fa, t); mma_sc<1>(fb, b1, kf, vf); sm_quarter<2, 3, false>(b0, t, pa[3], da[3]); S2_PHASE_END(3, 4);
+  // 13-14: accumulate(2) | softmax(3) first half
+  load_acc<2, 1>(fb, t); mma_acc<0>(fa, pa, da, dk_acc, dv_acc); sm_quarter<3, 0, false>(b1, t, pb[0], db[0]); S2_PHASE_END(3, 4);
+  load_acc<3, 0>(fa, t); mma_acc<1>(fb, pa, da, dk_acc, dv_acc); sm_quarter<3, 1, false>(b1, t, pb[1], db[1]); S2_PHASE_END(3, 4);
+  // 15-16: accumulate(3) | softmax(3) second half
+  load_acc<3, 1>(fb, t); mma_acc<0>(fa, pb, db, dk_acc, dv_acc);
+  sm_quarter<3, 2, false>(b1, t, pb[2], db[2]); sm_quarter<3, 3, false>(b1, t, pb[3], db[3]); S2_PHASE_END(3, 8);
+  mma_acc<1>(fb, pb, db, dk_acc, dv_acc);
+  __builtin_amdgcn_sched_barrier(0);
+#undef S2_PHASE_END
+}
+
+// One 32-query block without pipelining (diagonal tiles).
 template <bool MASK>
-__device__ __forceinline__ void dkdv_softmax(const DkdvBlock& blk, const float* lse_s, const float* delta_s, int mb,
-                                             int q_first, int key, float c2, int g32,
-                                             bf16x8 (&pf)[2], bf16x8 (&dsf)[2]) {
-  float p[16], ds[16];
-#pragma unroll
-  for (int vv = 0; vv < 4; ++vv) {
-    const float4 l4 = *reinterpret_cast<const float4*>(lse_s + 32 * mb + 8 * vv + 4 * g32);
-    const float4 d4 = *reinterpret_cast<const float4*>(delta_s + 32 * mb + 8 * vv + 4 * g32);
-    const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int v = 4 * vv + e;
-      float pv = __builtin_amdgcn_exp2f(fmaf(blk.s[v], c2, -ls[e] * kLog2e));
-      if (MASK) {
-        const int qrow = q_first + 8 * vv + 4 * g32 + e;
-        if (key > qrow) pv = 0.f;
-      }
-      p[v] = pv;
-      ds[v] = pv * (blk.dp[v] - dl[e]);
-    }
-  }
-  pf[0] = pack8(p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]);
-  pf[1] = pack8(p[8], p[9], p[10], p[11], p[12], p[13], p[14], p[15]);
-  dsf[0] = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
-  dsf[1] = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
-}
-
-// dV^T += dO^T P and dK^T += Q^T dS for query block mb.
-__device__ __forceinline__ void dkdv_accumulate(f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4], const char* Qs,
-                                                const char* dOs, int mb, const bf16x8 (&pf)[2],
-                                                const bf16x8 (&dsf)[2], int lane) {
-#pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    bf16x8 dot[4], qt[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      dot[db] = frag_tr(dOs, 32 * mb + 16 * t, db, lane);
-      qt[db] = frag_tr(Qs, 32 * mb + 16 * t, db, lane);
-    }
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      dv_acc[db] = mfma32(dot[db], pf[t], dv_acc[db]);
-      dk_acc[db] = mfma32(qt[db], dsf[t], dk_acc[db]);
-    }
-  }
+__device__ __forceinline__ void dkdv_block(const DkdvTile& t, int mb, int q_first, int key, const bf16x8 (&kf)[8],
+                                           const bf16x8 (&vf)[8], f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4]) {
+  DkdvTile tt = t;
+  tt.Qs += mb * 32 * kRowBytes;     // rows of a tile are swizzled by (row & 15) only, so a
+  tt.dOs += mb * 32 * kRowBytes;    // block is addressed by moving the base by 32 rows
+  tt.lse2_s += 32 * mb;
+  tt.delta_s += 32 * mb;
+  bf16x8 fa[8], fb[8];
+  DkdvBlock blk;
+  bf16x4 pq[4], dsq[4];
+  blk.s = zero16(); blk.dp = zero16();
+  load_sc<0, 0>(fa, tt); load_sc<0, 1>(fb, tt);
+  mma_sc<0>(fa, blk, kf, vf); mma_sc<1>(fb, blk, kf, vf);
+  load_acc<0, 0>(fa, tt); load_acc<0, 1>(fb, tt);
+  sm_quarter<0, 0, MASK>(blk, tt, pq[0], dsq[0], q_first, key);
+  sm_quarter<0, 1, MASK>(blk, tt, pq[1], dsq[1], q_first, key);
+  sm_quarter<0, 2, MASK>(blk, tt, pq[2], dsq[2], q_first, key);
+  sm_quarter<0, 3, MASK>(blk, tt, pq[3], dsq[3], q_first, key);
+  mma_acc<0>(fa, pq, dsq, dk_acc, dv_acc);
+  mma_acc<1>(fb, pq, dsq, dk_acc, dv_acc);
 }
 
 __global__ void __launch_bounds__(256, 1)
 bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
   __shared__ __attribute__((aligned(1024))) char smem[4 * kQTileBytes];            // [stage][Q,dO]
-  __shared__ __attribute__((aligned(1024))) float rows_s[2][2][kQTileRows];        // [stage][lse, delta]
+  __shared__ __attribute__((aligned(1024))) float rows_s[2][2][kQTileRows];        // [stage][lse * log2(e), delta]
 
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g32 = lane >> 5, l32 = lane & 31;
@@ -189,7 +261,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
       }
       if (w == hf) {   // wave 0 / 1: lse and delta of rows 64*hf .. +63
         const size_t ro = ((size_t)b * a.H + h) * a.N + tok0 + lane;
-        dma4(a.lse + ro, rows_base + ((stage * 2 + 0) * kQTileRows + 64 * hf) * 4);
+        dma4(a.lse2 + ro, rows_base + ((stage * 2 + 0) * kQTileRows + 64 * hf) * 4);
         dma4(a.delta + ro, rows_base + ((stage * 2 + 1) * kQTileRows + 64 * hf) * 4);
       }
     }
@@ -206,51 +278,20 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
     __syncthreads();
     if (n + 1 < n_iter) issue_tile(n + 1, stage ^ 1);
     const int q0 = (it_begin + n % nq) * kQTileRows;
-    const char* Qs = smem + stage * 2 * kQTileBytes;
-    const char* dOs = Qs + kQTileBytes;
-    const float* lse_s = rows_s[stage][0];
-    const float* delta_s = rows_s[stage][1];
+    DkdvTile t;
+    t.Qs = smem + stage * 2 * kQTileBytes;
+    t.dOs = t.Qs + kQTileBytes;
+    t.lse2_s = rows_s[stage][0];
+    t.delta_s = rows_s[stage][1];
+    t.c2 = c2; t.lane = lane; t.l32 = l32; t.g32 = g32;
     // Variant 2: keys of the first block see no query of the second block
     if (kw0 + 31 < split && q0 >= split) continue;
     if (q0 > j0) {
-      // interior tile: all four blocks fully visible; blocks software-pipelined
-      // MFMA order: sc0 sc1 acc0 sc2 acc1 sc3 acc2 acc3, with the VALU work of block n
-      // (P, dS) placed beside the MFMA group that precedes acc(n).
-      DkdvBlock b0, b1;
-      bf16x8 pfa[2], dsfa[2], pfb[2], dsfb[2];
-      dkdv_scores(b0, Qs, dOs, 0, kf, vf, l32, g32);
-      __builtin_amdgcn_sched_barrier(0);
-      dkdv_scores(b1, Qs, dOs, 1, kf, vf, l32, g32);
-      dkdv_softmax<false>(b0, lse_s, delta_s, 0, 0, key, c2, g32, pfa, dsfa);
-      interleave_mfma<16, 2, 9>();
-      __builtin_amdgcn_sched_barrier(0);
-      dkdv_accumulate(dk_acc, dv_acc, Qs, dOs, 0, pfa, dsfa, lane);
-      dkdv_softmax<false>(b1, lse_s, delta_s, 1, 0, key, c2, g32, pfb, dsfb);
-      interleave_mfma<16, 3, 9>();
-      __builtin_amdgcn_sched_barrier(0);
-      dkdv_scores(b0, Qs, dOs, 2, kf, vf, l32, g32);
-      __builtin_amdgcn_sched_barrier(0);
-      dkdv_accumulate(dk_acc, dv_acc, Qs, dOs, 1, pfb, dsfb, lane);
-      dkdv_softmax<false>(b0, lse_s, delta_s, 2, 0, key, c2, g32, pfa, dsfa);
-      interleave_mfma<16, 3, 9>();
-      __builtin_amdgcn_sched_barrier(0);
-      dkdv_scores(b1, Qs, dOs, 3, kf, vf, l32, g32);
-      __builtin_amdgcn_sched_barrier(0);
-      dkdv_accumulate(dk_acc, dv_acc, Qs, dOs, 2, pfa, dsfa, lane);
-      dkdv_softmax<false>(b1, lse_s, delta_s, 3, 0, key, c2, g32, pfb, dsfb);
-      interleave_mfma<16, 3, 9>();
-      __builtin_amdgcn_sched_barrier(0);
-      dkdv_accumulate(dk_acc, dv_acc, Qs, dOs, 3, pfb, dsfb, lane);
+      dkdv_interior_tile(t, kf, vf, dk_acc, dv_acc);
     } else {
       // diagonal tile: block mb < w is entirely before this wave's keys, block w is masked
-      for (int mb = w; mb < 4; ++mb) {
-        DkdvBlock blk;
-        bf16x8 pf[2], dsf[2];
-        dkdv_scores(blk, Qs, dOs, mb, kf, vf, l32, g32);
-        if (mb == w) dkdv_softmax<true>(blk, lse_s, delta_s, mb, q0 + 32 * mb, key, c2, g32, pf, dsf);
-        else dkdv_softmax<false>(blk, lse_s, delta_s, mb, 0, key, c2, g32, pf, dsf);
-        dkdv_accumulate(dk_acc, dv_acc, Qs, dOs, mb, pf, dsf, lane);
-      }
+      dkdv_block<true>(t, w, q0 + 32 * w, key, kf, vf, dk_acc, dv_acc);
+      for (int mb = w + 1; mb < 4; ++mb) dkdv_block<false>(t, mb, 0, key, kf, vf, dk_acc, dv_acc);
     }
   }
   __syncthreads();
@@ -386,7 +427,7 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
 #pragma unroll
     for (int st = 0; st < 8; ++st) { qf[st] = qsrc[2 * st + g32]; dof[st] = dsrc[2 * st + g32]; }
     const size_t ro = ((size_t)b * a.H + h) * a.N + tok;
-    lse2 = a.lse[ro] * kLog2e;
+    lse2 = a.lse2[ro];
     delta = a.delta[ro];
   }
 

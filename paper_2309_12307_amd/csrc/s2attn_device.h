@@ -12,6 +12,7 @@ struct KArgs {
   const void* dout;
   void* dq; void* dk; void* dv;
   float* delta;                              // (B,H,N) fp32
+  float* lse2;                               // (B,H,N) fp32: lse * log2(e), written by the pre-pass
   float* dkv_partial;                        // fp32 [2 tensors][2 classes][B,N,Hkv,D] or null
   int B, N, H, Hkv, D, G;
   int r;                                     // H / Hkv

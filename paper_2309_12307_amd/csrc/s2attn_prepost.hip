@@ -1,5 +1,6 @@
 // Backward pre- and post-passes shared by the fp32 and bf16 paths.
-//   delta:   the row term of the softmax Jacobian, delta_i = sum_j P_ij dP_ij = dO_i . O_i
+//   delta:   the row term of the softmax Jacobian, delta_i = sum_j P_ij dP_ij = dO_i . O_i;
+//            the same pass rescales lse to base 2 for the kernels' exp2
 //   combine: sum of the two per-class fp32 partials of dK/dV when one kv head serves
 //            both shifted and unshifted query heads.
 // Both are pure streaming kernels (HBM-bound, 16-byte coalesced accesses).
@@ -20,8 +21,8 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {   // round to ne
 
 // 16 lanes per (b,t,h) row; each lane reads 16-byte chunks.
 template <bool BF16>
-__global__ void __launch_bounds__(256) delta_kernel(const void* o, const void* dout, float* delta,
-                                                    int B, int N, int H, int D) {
+__global__ void __launch_bounds__(256) delta_kernel(const void* o, const void* dout, const float* lse,
+                                                    float* delta, float* lse2, int B, int N, int H, int D) {
   const size_t row = (size_t)blockIdx.x * 16 + threadIdx.x / 16;
   const int lane = threadIdx.x % 16;
   const size_t rows = (size_t)B * N * H;
@@ -57,6 +58,7 @@ __global__ void __launch_bounds__(256) delta_kernel(const void* o, const void* d
     const int h = (int)(row % H);
     const size_t b = bt / N, t = bt % N;
     delta[(b * H + h) * N + t] = acc;
+    lse2[(b * H + h) * N + t] = lse[(b * H + h) * N + t] * 1.4426950408889634f;
   }
 }
 
@@ -87,9 +89,9 @@ int launch_delta(const KArgs& a, int dtype, hipStream_t st) {
   const size_t rows = (size_t)a.B * a.N * a.H;
   dim3 grid((unsigned)((rows + 15) / 16));
   if (dtype == S2ATTN_BF16)
-    hipLaunchKernelGGL(delta_kernel<true>, grid, dim3(256), 0, st, a.o, a.dout, a.delta, a.B, a.N, a.H, a.D);
+    hipLaunchKernelGGL(delta_kernel<true>, grid, dim3(256), 0, st, a.o, a.dout, a.lse, a.delta, a.lse2, a.B, a.N, a.H, a.D);
   else
-    hipLaunchKernelGGL(delta_kernel<false>, grid, dim3(256), 0, st, a.o, a.dout, a.delta, a.B, a.N, a.H, a.D);
+    hipLaunchKernelGGL(delta_kernel<false>, grid, dim3(256), 0, st, a.o, a.dout, a.lse, a.delta, a.lse2, a.B, a.N, a.H, a.D);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

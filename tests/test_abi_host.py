@@ -93,11 +93,11 @@ def test_forward_check_ignores_backward_fields():
 
 
 def test_workspace_size():
-    # delta only: B*H*N floats rounded to 256 bytes
-    assert binding.bwd_workspace_bytes(1, 32768, 32, 32, 128, 8192) == 32 * 32768 * 4
+    # delta and base-2 lse: 2 * B*H*N floats (each rounded to 256 bytes)
+    assert binding.bwd_workspace_bytes(1, 32768, 32, 32, 128, 8192) == 2 * 32 * 32768 * 4
     # MQA: one kv head serves shifted and unshifted heads -> fp32 partials too
     w = binding.bwd_workspace_bytes(1, 256, 4, 1, 64, 64, binding.F32)
-    assert w == 4 * 256 * 4 + 4 * 256 * 64 * 4
+    assert w == 2 * 4 * 256 * 4 + 4 * 256 * 64 * 4
 
 
 def test_missing_library_is_an_error(monkeypatch, tmp_path):
