@@ -51,7 +51,8 @@ struct DkdvTile {      // the staged query tile and per-lane constants
   const float* lse2_s;
   const float* delta_s;
   float c2;
-  int lane, l32, g32;
+  int g32;
+  LaneOffsets lo;
 };
 
 // ---- fragment loads and MFMA groups, one "phase" = 8 MFMAs fed by 8 fragments
@@ -60,8 +61,8 @@ template <int MB, int H>
 __device__ __forceinline__ void load_sc(bf16x8 (&buf)[8], const DkdvTile& t) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    buf[i] = frag_rm(t.Qs, 32 * MB + t.l32, 2 * (4 * H + i) + t.g32);
-    buf[4 + i] = frag_rm(t.dOs, 32 * MB + t.l32, 2 * (4 * H + i) + t.g32);
+    buf[i] = frag_rm<32 * MB>(t.Qs, t.lo, 4 * H + i);
+    buf[4 + i] = frag_rm<32 * MB>(t.dOs, t.lo, 4 * H + i);
   }
 }
 template <int H>
@@ -78,8 +79,8 @@ template <int MB, int T>
 __device__ __forceinline__ void load_acc(bf16x8 (&buf)[8], const DkdvTile& t) {
 #pragma unroll
   for (int db = 0; db < 4; ++db) {
-    buf[db] = frag_tr(t.dOs, 32 * MB + 16 * T, db, t.lane);
-    buf[4 + db] = frag_tr(t.Qs, 32 * MB + 16 * T, db, t.lane);
+    buf[db] = frag_tr<32 * MB + 16 * T>(t.dOs, t.lo, db);
+    buf[4 + db] = frag_tr<32 * MB + 16 * T>(t.Qs, t.lo, db);
   }
 }
 template <int T>
@@ -267,6 +268,8 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
     }
   };
 
+  LaneOffsets lo;
+  init_lane_offsets(lo, lane);
   f32x16 dk_acc[4], dv_acc[4];
 #pragma unroll
   for (int db = 0; db < 4; ++db) { dk_acc[db] = zero16(); dv_acc[db] = zero16(); }
@@ -283,7 +286,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
     t.dOs = t.Qs + kQTileBytes;
     t.lse2_s = rows_s[stage][0];
     t.delta_s = rows_s[stage][1];
-    t.c2 = c2; t.lane = lane; t.l32 = l32; t.g32 = g32;
+    t.c2 = c2; t.g32 = g32; t.lo = lo;
     // Variant 2: keys of the first block see no query of the second block
     if (kw0 + 31 < split && q0 >= split) continue;
     if (q0 > j0) {
@@ -340,48 +343,60 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
 constexpr int BN = 64;                       // keys per tile
 constexpr int kTileBytes = BN * kRowBytes;   // 16 KB
 
+// dS^T of the 32 keys starting at tile row ROW0, as two packed B operands.
+template <int ROW0, bool MASK>
+__device__ __forceinline__ void dq_scores(bf16x8& ds_lo, bf16x8& ds_hi, const bf16x8 (&qf)[8], const bf16x8 (&dof)[8],
+                                          const char* Ks, const char* Vs, const LaneOffsets& lo, int j0, int qrow,
+                                          float c2, float lse2, float delta, int g32) {
+  f32x16 sa = zero16(), pa = zero16();
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    bf16x8 kr[4], vr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      kr[i] = frag_rm<ROW0>(Ks, lo, 4 * half + i);
+      vr[i] = frag_rm<ROW0>(Vs, lo, 4 * half + i);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      sa = mfma32(kr[i], qf[4 * half + i], sa);
+      pa = mfma32(vr[i], dof[4 * half + i], pa);
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    float e = __builtin_amdgcn_exp2f(fmaf(sa[v], c2, -lse2));
+    if (MASK) {
+      const int key = j0 + ROW0 + 8 * (v >> 2) + 4 * g32 + (v & 3);
+      if (key > qrow) e = 0.f;
+    }
+    sa[v] = e * (pa[v] - delta);
+  }
+  ds_lo = pack8(sa[0], sa[1], sa[2], sa[3], sa[4], sa[5], sa[6], sa[7]);
+  ds_hi = pack8(sa[8], sa[9], sa[10], sa[11], sa[12], sa[13], sa[14], sa[15]);
+}
+
+// dQ^T += K^T dS^T for the 16 keys starting at tile row KROW0.
+template <int KROW0>
+__device__ __forceinline__ void dq_step(f32x16 (&dq_acc)[4], const char* Ks, const LaneOffsets& lo, bf16x8 dsf) {
+  bf16x8 kt[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db) kt[db] = frag_tr<KROW0>(Ks, lo, db);
+#pragma unroll
+  for (int db = 0; db < 4; ++db) dq_acc[db] = mfma32(kt[db], dsf, dq_acc[db]);
+}
+
 template <bool MASK>
 __device__ __forceinline__ void dq_tile(f32x16 (&dq_acc)[4], const bf16x8 (&qf)[8], const bf16x8 (&dof)[8],
-                                        const char* Ks, const char* Vs, int j0, int qrow, float c2,
-                                        float lse2, float delta, int lane, int l32, int g32) {
+                                        const char* Ks, const char* Vs, const LaneOffsets& lo, int j0,
+                                        int qrow, float c2, float lse2, float delta, int g32) {
   bf16x8 dsf[4];
-#pragma unroll
-  for (int mb = 0; mb < 2; ++mb) {
-    f32x16 sa = zero16(), pa = zero16();
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      bf16x8 kr[4], vr[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        kr[i] = frag_rm(Ks, 32 * mb + l32, 2 * (4 * half + i) + g32);
-        vr[i] = frag_rm(Vs, 32 * mb + l32, 2 * (4 * half + i) + g32);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        sa = mfma32(kr[i], qf[4 * half + i], sa);
-        pa = mfma32(vr[i], dof[4 * half + i], pa);
-      }
-    }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      float e = __builtin_amdgcn_exp2f(fmaf(sa[v], c2, -lse2));
-      if (MASK) {
-        const int key = j0 + 32 * mb + 8 * (v >> 2) + 4 * g32 + (v & 3);
-        if (key > qrow) e = 0.f;
-      }
-      sa[v] = e * (pa[v] - delta);
-    }
-    dsf[2 * mb] = pack8(sa[0], sa[1], sa[2], sa[3], sa[4], sa[5], sa[6], sa[7]);
-    dsf[2 * mb + 1] = pack8(sa[8], sa[9], sa[10], sa[11], sa[12], sa[13], sa[14], sa[15]);
-  }
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    bf16x8 kt[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db) kt[db] = frag_tr(Ks, 16 * ks, db, lane);
-#pragma unroll
-    for (int db = 0; db < 4; ++db) dq_acc[db] = mfma32(kt[db], dsf[ks], dq_acc[db]);
-  }
+  dq_scores<0, MASK>(dsf[0], dsf[1], qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32);
+  dq_scores<32, MASK>(dsf[2], dsf[3], qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32);
+  dq_step<0>(dq_acc, Ks, lo, dsf[0]);
+  dq_step<16>(dq_acc, Ks, lo, dsf[1]);
+  dq_step<32>(dq_acc, Ks, lo, dsf[2]);
+  dq_step<48>(dq_acc, Ks, lo, dsf[3]);
 }
 
 __global__ void __launch_bounds__(256, 2)
@@ -446,6 +461,8 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
     }
   };
 
+  LaneOffsets lo;
+  init_lane_offsets(lo, lane);
   f32x16 dq_acc[4];
 #pragma unroll
   for (int db = 0; db < 4; ++db) dq_acc[db] = zero16();
@@ -463,9 +480,9 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
     const char* Vs = Ks + kTileBytes;
     if (j0 + BN - 1 < lo_w) continue;
     if (jt < jt_diag || (jt == jt_diag && w >= 2)) {
-      dq_tile<false>(dq_acc, qf, dof, Ks, Vs, j0, qrow, c2, lse2, delta, lane, l32, g32);
+      dq_tile<false>(dq_acc, qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32);
     } else if (jt == jt_diag || w >= 2) {
-      dq_tile<true>(dq_acc, qf, dof, Ks, Vs, j0, qrow, c2, lse2, delta, lane, l32, g32);
+      dq_tile<true>(dq_acc, qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32);
     }
   }
   __syncthreads();

@@ -38,26 +38,50 @@ __device__ __forceinline__ int tile_off(int row, int chunk) {
   return row * kRowBytes + ((chunk ^ swz(row)) << 4);
 }
 
-// Row-major operand fragment: elements [8*chunk, 8*chunk+8) of `row`.
-__device__ __forceinline__ bf16x8 frag_rm(const char* tile, int row, int chunk) {
-  return *reinterpret_cast<const bf16x8*>(tile + tile_off(row, chunk));
+// Per-lane byte offsets of the two kinds of operand fragments inside a tile, computed
+// once per kernel.  Because the swizzle depends on (row mod 16) only, a fragment of a
+// row block that starts at a multiple of 16 rows is the same offset plus a constant,
+// which the compiler folds into the LDS instruction's immediate offset.
+struct LaneOffsets {
+  int rm[8];      // row-major fragment k: elements [16k + 8g, +8) of row (l % 32)
+  int tr[4][2];   // transposed fragment, column block cb: rows 4g + L/4 and that + 8
+};
+
+__device__ __forceinline__ void init_lane_offsets(LaneOffsets& o, int lane) {
+  const int l32 = lane & 31, g32 = lane >> 5;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) o.rm[k] = tile_off(l32, 2 * k + g32);
+  const int L = lane & 15, half = lane & 16;
+  const int row = 4 * g32 + (L >> 2);
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb) {
+    const int col = 32 * cb + half + 4 * (L & 3);
+    const int chunk = col >> 3, within = (col & 7) * 2;
+    o.tr[cb][0] = row * kRowBytes + ((chunk ^ swz(row)) << 4) + within;
+    o.tr[cb][1] = (row + 8) * kRowBytes + ((chunk ^ swz(row + 8)) << 4) + within;
+  }
+}
+
+// Row-major operand fragment k (elements [16k + 8g, +8)) of row ROW0 + (l % 32);
+// ROW0 must be a multiple of 16.
+template <int ROW0>
+__device__ __forceinline__ bf16x8 frag_rm(const char* tile, const LaneOffsets& o, int k) {
+  static_assert(ROW0 % 16 == 0, "row block must start at a multiple of 16 rows");
+  return *reinterpret_cast<const bf16x8*>(tile + o.rm[k] + ROW0 * kRowBytes);
 }
 
 // Transposed operand fragment: the operand row index runs along the tile's columns
-// (32 columns starting at 32*cb) and the contraction index along 16 tile rows starting
-// at krow0, in the accumulator-feedback order described above.  Two transposing
-// 64-bit LDS reads: within each block of 16 lanes, lane L points at 4 elements of tile
-// row (L / 4) and receives one column of the 4 rows.
-__device__ __forceinline__ bf16x8 frag_tr(const char* tile, int krow0, int cb, int lane) {
-  const int g = lane >> 5, L = lane & 15, half = lane & 16;
-  const int row = krow0 + 4 * g + (L >> 2);
-  const int col = 32 * cb + half + 4 * (L & 3);
-  const int chunk = col >> 3, within = (col & 7) * 2;
+// (32 columns starting at 32*cb) and the contraction index along the 16 tile rows
+// starting at KROW0 (a multiple of 16), in the accumulator-feedback order described
+// above.  Two transposing 64-bit LDS reads: within each block of 16 lanes, lane L
+// points at 4 elements of tile row (L / 4) and receives one column of the 4 rows.
+template <int KROW0>
+__device__ __forceinline__ bf16x8 frag_tr(const char* tile, const LaneOffsets& o, int cb) {
+  static_assert(KROW0 % 16 == 0, "row block must start at a multiple of 16 rows");
   const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-      S2_LDS(bf16x4, tile + row * kRowBytes + ((chunk ^ swz(row)) << 4) + within));
-  const int row2 = row + 8;
+      S2_LDS(bf16x4, tile + o.tr[cb][0] + KROW0 * kRowBytes));
   const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-      S2_LDS(bf16x4, tile + row2 * kRowBytes + ((chunk ^ swz(row2)) << 4) + within));
+      S2_LDS(bf16x4, tile + o.tr[cb][1] + KROW0 * kRowBytes));
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 

@@ -31,18 +31,28 @@ struct FwdState {
   float l_run;    // this lane's part of the running row sum
 };
 
+// O^T += V^T P^T for the 16 keys starting at tile row KROW0.
+template <int KROW0>
+__device__ __forceinline__ void pv_step(FwdState& st, const char* Vs, const LaneOffsets& lo, bf16x8 pf) {
+  bf16x8 vf[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db) vf[db] = frag_tr<KROW0>(Vs, lo, db);
+#pragma unroll
+  for (int db = 0; db < 4; ++db) st.o_acc[db] = mfma32(vf[db], pf, st.o_acc[db]);
+}
+
 // One 64-key tile for one wave (32 queries).
 template <bool MASK>
 __device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], const char* Ks, const char* Vs,
-                                         int j0, int qrow, float c2, int lane, int l32, int g32) {
+                                         const LaneOffsets& lo, int j0, int qrow, float c2, int g32) {
   // ---- S^T = K Q^T: two 32-key blocks
   f32x16 s0 = zero16(), s1 = zero16();
   {
     bf16x8 ka[4], kb[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      ka[i] = frag_rm(Ks, l32, 2 * i + g32);
-      kb[i] = frag_rm(Ks, 32 + l32, 2 * i + g32);
+      ka[i] = frag_rm<0>(Ks, lo, i);
+      kb[i] = frag_rm<32>(Ks, lo, i);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -51,8 +61,8 @@ __device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], co
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      ka[i] = frag_rm(Ks, l32, 2 * (i + 4) + g32);
-      kb[i] = frag_rm(Ks, 32 + l32, 2 * (i + 4) + g32);
+      ka[i] = frag_rm<0>(Ks, lo, i + 4);
+      kb[i] = frag_rm<32>(Ks, lo, i + 4);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -98,14 +108,10 @@ __device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], co
   pf[2] = pack8(s1[0], s1[1], s1[2], s1[3], s1[4], s1[5], s1[6], s1[7]);
   pf[3] = pack8(s1[8], s1[9], s1[10], s1[11], s1[12], s1[13], s1[14], s1[15]);
   // ---- O^T += V^T P^T
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    bf16x8 vf[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db) vf[db] = frag_tr(Vs, 16 * ks, db, lane);
-#pragma unroll
-    for (int db = 0; db < 4; ++db) st.o_acc[db] = mfma32(vf[db], pf[ks], st.o_acc[db]);
-  }
+  pv_step<0>(st, Vs, lo, pf[0]);
+  pv_step<16>(st, Vs, lo, pf[1]);
+  pv_step<32>(st, Vs, lo, pf[2]);
+  pv_step<48>(st, Vs, lo, pf[3]);
 }
 
 __global__ void __launch_bounds__(256, 2)
@@ -179,6 +185,8 @@ fwd_bf16_kernel(KArgs a, int T, int n_rest) {
     }
   };
 
+  LaneOffsets lo;
+  init_lane_offsets(lo, lane);
   FwdState st;
   st.m_run = -INFINITY;
   st.l_run = 0.f;
@@ -198,9 +206,9 @@ fwd_bf16_kernel(KArgs a, int T, int n_rest) {
     const char* Vs = Ks + kTileBytes;
     if (j0 + BN - 1 < lo_w) continue;               // Variant 2: keys of the other block
     if (jt < jt_diag || (jt == jt_diag && w >= 2)) {
-      fwd_tile<false>(st, qf, Ks, Vs, j0, qrow, c2, lane, l32, g32);
+      fwd_tile<false>(st, qf, Ks, Vs, lo, j0, qrow, c2, g32);
     } else if (jt == jt_diag || w >= 2) {
-      fwd_tile<true>(st, qf, Ks, Vs, j0, qrow, c2, lane, l32, g32);
+      fwd_tile<true>(st, qf, Ks, Vs, lo, j0, qrow, c2, g32);
     }
   }
   __syncthreads();
