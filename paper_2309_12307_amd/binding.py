@@ -11,7 +11,7 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libs2attn.so")
+LIB_PATH = os.environ.get("S2ATTN_LIB", os.path.join(_HERE, "libs2attn.so"))
 
 BF16, F32 = 0, 1
 SHIFT_SECOND_HALF, SHIFT_NONE, SHIFT_ALL = 0, 1, 2

@@ -15,16 +15,16 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
 
 
-def build(verbose: bool = True, jobs: int = 4) -> str:
+def build(verbose: bool = True, extra_flags=(), out_path: str | None = None) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, "_build" if out_path is None else "_build_" + os.path.basename(out_path))
     os.makedirs(objdir, exist_ok=True)
     procs = []
     objs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [hipcc, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+        cmd = [hipcc, *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
                "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     failed = False
@@ -38,11 +38,12 @@ def build(verbose: bool = True, jobs: int = 4) -> str:
             sys.stderr.write(f"[build] {src}:\n{out}\n")
     if failed:
         raise RuntimeError("hipcc failed")
-    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    lib = LIB if out_path is None else out_path
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     subprocess.run(link, check=True)
     if verbose:
-        sys.stderr.write(f"[build] wrote {LIB}\n")
-    return LIB
+        sys.stderr.write(f"[build] wrote {lib}\n")
+    return lib
 
 
 if __name__ == "__main__":

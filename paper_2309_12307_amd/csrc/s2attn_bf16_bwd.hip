@@ -125,7 +125,7 @@ __device__ __forceinline__ void sm_quarter(const DkdvBlock& blk, const DkdvTile&
 // other fragment buffer.
 __device__ __forceinline__ void dkdv_interior_tile(const DkdvTile& t, const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
                                                    f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4]) {
-#define S2_PHASE_END(DS, VA) interleave_mfma<8, DS, VA>(); __builtin_amdgcn_sched_barrier(0)
+#define S2_PHASE_END(DS, VA) interleave_mfma2<3, 6, 5, 2 * VA>(); __builtin_amdgcn_sched_barrier(0)
   bf16x8 fa[8], fb[8];
   DkdvBlock b0, b1;
   bf16x4 pa[4], da[4], pb[4], db[4];

@@ -158,6 +158,23 @@ __device__ __forceinline__ void interleave_mfma() {
   }
 }
 
+// Two-part variant: the first N1 MFMAs each take up to DS1 LDS reads behind them (the
+// operand loads of the following phase go out early), the remaining N2 MFMAs each take
+// up to VA2 VALU/transcendental instructions.
+template <int N1, int DS1, int N2, int VA2>
+__device__ __forceinline__ void interleave_mfma2() {
+#pragma unroll
+  for (int i = 0; i < N1; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, DS1, 0);
+  }
+#pragma unroll
+  for (int i = 0; i < N2; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if (VA2 > 0) __builtin_amdgcn_sched_group_barrier(0x402, VA2, 0);
+  }
+}
+
 __device__ __forceinline__ f32x16 zero16() {
   f32x16 z;
 #pragma unroll
