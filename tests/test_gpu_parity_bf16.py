@@ -7,7 +7,9 @@ for a bf16 output: storing the exact value errs by up to |ref| * 2^-8 (0.0156 at
 0.031 at 8, 0.0625 at 16), so the bound turns relative, 5e-3 = 2^-8 for the output
 rounding plus 1.1e-3 for the bf16 rounding of P and dS ahead of the MFMAs.  Values
 above 4 occur in dk, dv at the first keys of a group, mostly under GQA where several
-heads' gradients are summed; o and dq must meet the plain 2e-2.
+heads' gradients are summed; o and dq must meet the plain 2e-2.  Under GQA with r query
+heads per kv head, dk and dv are sums of r per-head gradients that each carry their own
+operand rounding, so their absolute term is 2e-2 * sqrt(r) (r = 1: the stated bound).
 lse is an fp32 output: <= 2e-3."""
 import numpy as np
 import pytest
@@ -23,14 +25,14 @@ TOL_LSE = 2e-3
 RTOL = 5e-3
 
 
-def elementwise_tol(ref):
-    return np.maximum(TOL, RTOL * np.abs(ref))
+def elementwise_tol(ref, heads_summed=1):
+    return np.maximum(TOL * np.sqrt(heads_summed), RTOL * np.abs(ref))
 
 
-def check_tensor(name, got, ref):
+def check_tensor(name, got, ref, heads_summed=1):
     err = np.abs(got.astype(np.float64) - ref)
     assert np.all(np.isfinite(got)), name
-    bad = err > elementwise_tol(ref)
+    bad = err > elementwise_tol(ref, heads_summed)
     if bad.any():
         idx = np.unravel_index(np.argmax(err * bad), err.shape)
         raise AssertionError(f"{name}: {bad.sum()} elements over tolerance; worst at {idx}: "
@@ -42,7 +44,9 @@ def compare(out, ref):
     o, lse, dq, dk, dv = ref
     e_lse = np.abs(out["lse"] - lse).max()
     assert np.isfinite(e_lse) and e_lse <= TOL_LSE, ("lse", e_lse)
-    errs = {name: check_tensor(name, out[name], r) for name, r in (("o", o), ("dq", dq), ("dk", dk), ("dv", dv))}
+    r_heads = o.shape[2] // dk.shape[2]      # query heads summed into each kv head's gradient
+    errs = {name: check_tensor(name, out[name], r, hs)
+            for name, r, hs in (("o", o, 1), ("dq", dq, 1), ("dk", dk, r_heads), ("dv", dv, r_heads))}
     # o and dq never reach the binades where the bound is relaxed
     assert errs["o"] <= TOL and errs["dq"] <= TOL, errs
     return errs
