@@ -24,9 +24,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/),
-# keyed by workload then kernel; None until measured.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script,
+# scaled by a 1 GiB copy probe (profiles/s2attn_fwd_bwd_C3_rocprofv3.md), keyed by workload
+# then kernel.  Not measurable from inside the process; null for workloads not profiled.
+MEASURED_TRAFFIC = {
+    "C3": {"fwd": 2.384e9, "bwd_dkdv": 2.346e9, "bwd_dq": 2.527e9},
+}
 
 
 class HipEvents:
@@ -64,7 +67,7 @@ class HipEvents:
         self.hip.hipEventDestroy(ev)
 
 
-def cpu_baseline(cfg, inp, budget_s=20.0):
+def cpu_baseline(cfg, inp, budget_s=15.0):
     """The oracle as it stands, on a bounded sample: whole (kv head, group) slices of the
     workload, forward + backward in fp32, until about `budget_s` seconds are spent."""
     from oracle import s2attn_oracle as orc
@@ -75,7 +78,7 @@ def cpu_baseline(cfg, inp, budget_s=20.0):
         cores = os.cpu_count() or 1
     r = cfg.H // cfg.Hkv
     pairs_per_slice = r * cfg.G * (cfg.G + 1) // 2
-    picks = [(0, 0), (cfg.Hkv - 1, cfg.N // cfg.G - 1), (cfg.Hkv - 1, 0), (0, cfg.N // cfg.G - 1)]
+    picks = [(c, g) for g in range(cfg.N // cfg.G) for c in range(cfg.Hkv)]
     done, t_total = 0, 0.0
     for c, g in picks:
         t0 = time.perf_counter()
@@ -99,6 +102,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", help="C2 | C3 | C4 | C5 (bf16 configurations)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this "
+                         "command holds a kernel of known HBM traffic to scale FETCH_SIZE/WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU S2-Attn kernels only: this build has no multi-GPU path "
@@ -143,6 +149,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     marks = [[ev.create() for _ in range(5)] for _ in range(args.steps)]
     torch.cuda.synchronize()
