@@ -41,10 +41,10 @@ __device__ __forceinline__ void pv_step(FwdState& st, const char* Vs, const Lane
   for (int db = 0; db < 4; ++db) st.o_acc[db] = mfma32(vf[db], pf, st.o_acc[db]);
 }
 
-// One 64-key tile for one wave (32 queries).
-template <bool MASK>
+// One 64-key tile for one wave (32 queries).  `masked` is wave-uniform: the tile
+// touches the diagonal of this wave's rows and needs the causal mask.
 __device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], const char* Ks, const char* Vs,
-                                         const LaneOffsets& lo, int j0, int qrow, float c2, int g32) {
+                                         const LaneOffsets& lo, int j0, int qrow, float c2, int g32, bool masked) {
   // ---- S^T = K Q^T: two 32-key blocks
   f32x16 s0 = zero16(), s1 = zero16();
   {
@@ -70,7 +70,7 @@ __device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], co
       s1 = mfma32(kb[i], qf[i + 4], s1);
     }
   }
-  if (MASK) {
+  if (masked) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int key = j0 + 8 * (v >> 2) + 4 * g32 + (v & 3);
@@ -204,12 +204,10 @@ fwd_bf16_kernel(KArgs a, int T, int n_rest) {
     const int j0 = jt * BN;
     const char* Ks = smem + stage * 2 * kTileBytes;
     const char* Vs = Ks + kTileBytes;
-    if (j0 + BN - 1 < lo_w) continue;               // Variant 2: keys of the other block
-    if (jt < jt_diag || (jt == jt_diag && w >= 2)) {
-      fwd_tile<false>(st, qf, Ks, Vs, lo, j0, qrow, c2, g32);
-    } else if (jt == jt_diag || w >= 2) {
-      fwd_tile<true>(st, qf, Ks, Vs, lo, j0, qrow, c2, g32);
-    }
+    // this wave's rows see keys [lo_w, row]: skip tiles wholly outside (beyond the
+    // diagonal, or, under Variant 2, in the other block of the wrap group)
+    if (j0 > qw0 + 31 || j0 + BN - 1 < lo_w) continue;
+    fwd_tile(st, qf, Ks, Vs, lo, j0, qrow, c2, g32, j0 + BN - 1 > qw0);
   }
   __syncthreads();
 
