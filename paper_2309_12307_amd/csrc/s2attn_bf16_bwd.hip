@@ -344,10 +344,10 @@ constexpr int BN = 64;                       // keys per tile
 constexpr int kTileBytes = BN * kRowBytes;   // 16 KB
 
 // dS^T of the 32 keys starting at tile row ROW0, as two packed B operands.
-template <int ROW0, bool MASK>
+template <int ROW0>
 __device__ __forceinline__ void dq_scores(bf16x8& ds_lo, bf16x8& ds_hi, const bf16x8 (&qf)[8], const bf16x8 (&dof)[8],
                                           const char* Ks, const char* Vs, const LaneOffsets& lo, int j0, int qrow,
-                                          float c2, float lse2, float delta, int g32) {
+                                          float c2, float lse2, float delta, int g32, bool masked) {
   f32x16 sa = zero16(), pa = zero16();
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
@@ -363,15 +363,15 @@ __device__ __forceinline__ void dq_scores(bf16x8& ds_lo, bf16x8& ds_hi, const bf
       pa = mfma32(vr[i], dof[4 * half + i], pa);
     }
   }
+  if (masked) {   // wave-uniform: exp2(-inf) = 0 removes keys after the query
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    float e = __builtin_amdgcn_exp2f(fmaf(sa[v], c2, -lse2));
-    if (MASK) {
+    for (int v = 0; v < 16; ++v) {
       const int key = j0 + ROW0 + 8 * (v >> 2) + 4 * g32 + (v & 3);
-      if (key > qrow) e = 0.f;
+      if (key > qrow) sa[v] = -INFINITY;
     }
-    sa[v] = e * (pa[v] - delta);
   }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) sa[v] = __builtin_amdgcn_exp2f(fmaf(sa[v], c2, -lse2)) * (pa[v] - delta);
   ds_lo = pack8(sa[0], sa[1], sa[2], sa[3], sa[4], sa[5], sa[6], sa[7]);
   ds_hi = pack8(sa[8], sa[9], sa[10], sa[11], sa[12], sa[13], sa[14], sa[15]);
 }
@@ -386,13 +386,12 @@ __device__ __forceinline__ void dq_step(f32x16 (&dq_acc)[4], const char* Ks, con
   for (int db = 0; db < 4; ++db) dq_acc[db] = mfma32(kt[db], dsf, dq_acc[db]);
 }
 
-template <bool MASK>
 __device__ __forceinline__ void dq_tile(f32x16 (&dq_acc)[4], const bf16x8 (&qf)[8], const bf16x8 (&dof)[8],
                                         const char* Ks, const char* Vs, const LaneOffsets& lo, int j0,
-                                        int qrow, float c2, float lse2, float delta, int g32) {
+                                        int qrow, float c2, float lse2, float delta, int g32, bool masked) {
   bf16x8 dsf[4];
-  dq_scores<0, MASK>(dsf[0], dsf[1], qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32);
-  dq_scores<32, MASK>(dsf[2], dsf[3], qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32);
+  dq_scores<0>(dsf[0], dsf[1], qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32, masked);
+  dq_scores<32>(dsf[2], dsf[3], qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32, masked);
   dq_step<0>(dq_acc, Ks, lo, dsf[0]);
   dq_step<16>(dq_acc, Ks, lo, dsf[1]);
   dq_step<32>(dq_acc, Ks, lo, dsf[2]);
@@ -478,12 +477,8 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
     const int j0 = jt * BN;
     const char* Ks = smem + stage * 2 * kTileBytes;
     const char* Vs = Ks + kTileBytes;
-    if (j0 + BN - 1 < lo_w) continue;
-    if (jt < jt_diag || (jt == jt_diag && w >= 2)) {
-      dq_tile<false>(dq_acc, qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32);
-    } else if (jt == jt_diag || w >= 2) {
-      dq_tile<true>(dq_acc, qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32);
-    }
+    if (j0 > qw0 + 31 || j0 + BN - 1 < lo_w) continue;   // wholly outside this wave's visible keys
+    dq_tile(dq_acc, qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32, j0 + BN - 1 > qw0);
   }
   __syncthreads();
 
