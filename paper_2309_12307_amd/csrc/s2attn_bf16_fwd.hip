@@ -41,34 +41,32 @@ __device__ __forceinline__ void pv_step(FwdState& st, const char* Vs, const Lane
   for (int db = 0; db < 4; ++db) st.o_acc[db] = mfma32(vf[db], pf, st.o_acc[db]);
 }
 
-// One 64-key tile for one wave (32 queries).  `masked` is wave-uniform: the tile
-// touches the diagonal of this wave's rows and needs the causal mask.
-__device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], const char* Ks, const char* Vs,
-                                         const LaneOffsets& lo, int j0, int qrow, float c2, int g32, bool masked) {
-  // ---- S^T = K Q^T: two 32-key blocks
-  f32x16 s0 = zero16(), s1 = zero16();
-  {
-    bf16x8 ka[4], kb[4];
+// S^T = K Q^T of one 64-key tile for one wave (32 queries): two 32-key blocks.
+// `masked` is wave-uniform: the tile touches the diagonal of this wave's rows.
+__device__ __forceinline__ void fwd_scores(f32x16& s0, f32x16& s1, const bf16x8 (&qf)[8], const char* Ks,
+                                           const LaneOffsets& lo, int j0, int qrow, int g32, bool masked) {
+  s0 = zero16();
+  s1 = zero16();
+  bf16x8 ka[4], kb[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ka[i] = frag_rm<0>(Ks, lo, i);
-      kb[i] = frag_rm<32>(Ks, lo, i);
-    }
+  for (int i = 0; i < 4; ++i) {
+    ka[i] = frag_rm<0>(Ks, lo, i);
+    kb[i] = frag_rm<32>(Ks, lo, i);
+  }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      s0 = mfma32(ka[i], qf[i], s0);
-      s1 = mfma32(kb[i], qf[i], s1);
-    }
+  for (int i = 0; i < 4; ++i) {
+    s0 = mfma32(ka[i], qf[i], s0);
+    s1 = mfma32(kb[i], qf[i], s1);
+  }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ka[i] = frag_rm<0>(Ks, lo, i + 4);
-      kb[i] = frag_rm<32>(Ks, lo, i + 4);
-    }
+  for (int i = 0; i < 4; ++i) {
+    ka[i] = frag_rm<0>(Ks, lo, i + 4);
+    kb[i] = frag_rm<32>(Ks, lo, i + 4);
+  }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      s0 = mfma32(ka[i], qf[i + 4], s0);
-      s1 = mfma32(kb[i], qf[i + 4], s1);
-    }
+  for (int i = 0; i < 4; ++i) {
+    s0 = mfma32(ka[i], qf[i + 4], s0);
+    s1 = mfma32(kb[i], qf[i + 4], s1);
   }
   if (masked) {
 #pragma unroll
@@ -78,7 +76,11 @@ __device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], co
       if (key + 32 > qrow) s1[v] = -INFINITY;
     }
   }
-  // ---- online softmax
+}
+
+// Online softmax of the tile: updates the running maximum lazily, accumulates the row
+// sum and packs the probabilities as the four 16-key B operands of the PV product.
+__device__ __forceinline__ void fwd_softmax(FwdState& st, f32x16& s0, f32x16& s1, float c2, bf16x8 (&pf)[4]) {
   float mx = fmaxf(s0[0], s1[0]);
 #pragma unroll
   for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s0[v], s1[v]));
@@ -102,16 +104,57 @@ __device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], co
     rs += s0[v] + s1[v];
   }
   st.l_run += rs;
-  bf16x8 pf[4];
   pf[0] = pack8(s0[0], s0[1], s0[2], s0[3], s0[4], s0[5], s0[6], s0[7]);
   pf[1] = pack8(s0[8], s0[9], s0[10], s0[11], s0[12], s0[13], s0[14], s0[15]);
   pf[2] = pack8(s1[0], s1[1], s1[2], s1[3], s1[4], s1[5], s1[6], s1[7]);
   pf[3] = pack8(s1[8], s1[9], s1[10], s1[11], s1[12], s1[13], s1[14], s1[15]);
-  // ---- O^T += V^T P^T
+}
+
+// O^T += V^T P^T for the whole 64-key tile.
+__device__ __forceinline__ void fwd_pv(FwdState& st, const char* Vs, const LaneOffsets& lo, const bf16x8 (&pf)[4]) {
   pv_step<0>(st, Vs, lo, pf[0]);
   pv_step<16>(st, Vs, lo, pf[1]);
   pv_step<32>(st, Vs, lo, pf[2]);
   pv_step<48>(st, Vs, lo, pf[3]);
+}
+
+__device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], const char* Ks, const char* Vs,
+                                         const LaneOffsets& lo, int j0, int qrow, float c2, int g32, bool masked) {
+  f32x16 s0, s1;
+  bf16x8 pf[4];
+  fwd_scores(s0, s1, qf, Ks, lo, j0, qrow, g32, masked);
+  fwd_softmax(st, s0, s1, c2, pf);
+  fwd_pv(st, Vs, lo, pf);
+}
+
+// Normalises a wave's 32 x 128 output block, transposes it through the wave's private
+// 8 KB LDS region and stores it (and lse) at the un-rolled token rows.  Contains one
+// workgroup barrier between the LDS writes and reads.
+__device__ __forceinline__ void fwd_epilogue(const KArgs& a, FwdState& st, char* Os, int b, int h, int gidx, int s,
+                                             int qw0, float c2, int lane, int l32, int g32) {
+  __bf16* op = static_cast<__bf16*>(a.o);
+  const float l_tot = sum_halves(st.l_run);
+  const float inv = 1.f / l_tot;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int vv = 0; vv < 4; ++vv) {
+      const bf16x4 pk = pack4(st.o_acc[db][4 * vv] * inv, st.o_acc[db][4 * vv + 1] * inv,
+                              st.o_acc[db][4 * vv + 2] * inv, st.o_acc[db][4 * vv + 3] * inv);
+      *reinterpret_cast<bf16x4*>(Os + tile_off(l32, 4 * db + vv) + 8 * g32) = pk;
+    }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int row = it * 4 + (lane >> 4), ch = lane & 15;
+    const uint4 val = *reinterpret_cast<const uint4*>(Os + tile_off(row, ch));
+    const int tok = token_of(gidx * a.G + qw0 + row, s, a.N);
+    *reinterpret_cast<uint4*>(op + ((size_t)((size_t)b * a.N + tok) * a.H + h) * 128 + ch * 8) = val;
+  }
+  if (g32 == 0) {
+    const int tok = token_of(gidx * a.G + qw0 + l32, s, a.N);
+    a.lse[((size_t)b * a.H + h) * a.N + tok] = (st.m_run * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
+  }
 }
 
 __global__ void __launch_bounds__(256, 2)
@@ -212,35 +255,213 @@ fwd_bf16_kernel(KArgs a, int T, int n_rest) {
   __syncthreads();
 
   // ---- epilogue: normalise, transpose through LDS, store at un-rolled token rows
-  __bf16* op = static_cast<__bf16*>(a.o);
-  const float l_tot = sum_halves(st.l_run);
-  const float inv = 1.f / l_tot;
-  char* Os = smem + w * (32 * kRowBytes);
+  fwd_epilogue(a, st, smem + w * (32 * kRowBytes), b, h, gidx, s, qw0, c2, lane, l32, g32);
+}
+
+// ---- the matrix block of the eight-wave kernel as 8 steps of 4 MFMAs, each fed by 4
+// operand fragments.  Steps 0-3: O^T += V^T P^T for keys 16k .. 16k+15 of the current
+// tile; steps 4-7: S^T += K Q^T over d = 32(k-4) .. +31 of the next tile.
+template <int STEP>
+__device__ __forceinline__ void pp_load(bf16x8 (&buf)[4], const char* Vs_cur, const char* Ks_nxt, const LaneOffsets& lo) {
+  if constexpr (STEP < 4) {
 #pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int vv = 0; vv < 4; ++vv) {
-      const bf16x4 pk = pack4(st.o_acc[db][4 * vv] * inv, st.o_acc[db][4 * vv + 1] * inv,
-                              st.o_acc[db][4 * vv + 2] * inv, st.o_acc[db][4 * vv + 3] * inv);
-      *reinterpret_cast<bf16x4*>(Os + tile_off(l32, 4 * db + vv) + 8 * g32) = pk;
-    }
-  __syncthreads();
-#pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    const int row = it * 4 + (lane >> 4), ch = lane & 15;
-    const uint4 val = *reinterpret_cast<const uint4*>(Os + tile_off(row, ch));
-    const int tok = token_of(gidx * a.G + qw0 + row, s, a.N);
-    *reinterpret_cast<uint4*>(op + ((size_t)((size_t)b * a.N + tok) * a.H + h) * 128 + ch * 8) = val;
+    for (int db = 0; db < 4; ++db) buf[db] = frag_tr<16 * STEP>(Vs_cur, lo, db);
+  } else {
+    constexpr int J = STEP - 4;
+    buf[0] = frag_rm<0>(Ks_nxt, lo, 2 * J);
+    buf[1] = frag_rm<32>(Ks_nxt, lo, 2 * J);
+    buf[2] = frag_rm<0>(Ks_nxt, lo, 2 * J + 1);
+    buf[3] = frag_rm<32>(Ks_nxt, lo, 2 * J + 1);
   }
-  if (g32 == 0) {
+}
+
+template <int STEP>
+__device__ __forceinline__ void pp_mma(const bf16x8 (&buf)[4], FwdState& st, const bf16x8 (&pf)[4],
+                                       const bf16x8 (&qf)[8], f32x16& s0, f32x16& s1) {
+  if constexpr (STEP < 4) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db) st.o_acc[db] = mfma32(buf[db], pf[STEP], st.o_acc[db]);
+  } else {
+    constexpr int J = STEP - 4;
+    s0 = mfma32(buf[0], qf[2 * J], s0);
+    s1 = mfma32(buf[1], qf[2 * J], s1);
+    s0 = mfma32(buf[2], qf[2 * J + 1], s0);
+    s1 = mfma32(buf[3], qf[2 * J + 1], s1);
+  }
+}
+
+__device__ __forceinline__ void mask_scores(f32x16& s0, f32x16& s1, int j0, int qrow, int g32) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int key = j0 + 8 * (v >> 2) + 4 * g32 + (v & 3);
+    if (key > qrow) s0[v] = -INFINITY;
+    if (key + 32 > qrow) s1[v] = -INFINITY;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Eight-wave variant (G a multiple of 256): a workgroup owns 256 query rows and keeps
+// three K/V stages in LDS, one workgroup per CU, two waves per SIMD.  Each wave runs
+// the tile loop software-pipelined across tiles: the matrix block of an iteration is
+// P(n) V(n) followed by S(n+1) = K(n+1) Q^T, the vector block is the softmax of one
+// tile.  Waves 0-3 run the vector block after the matrix block, waves 4-7 before it,
+// so the two waves that share a SIMD alternate between the matrix and vector units
+// instead of competing for them ("ping-pong"), with a single barrier per tile.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(512, 1)
+fwd_bf16_pp_kernel(KArgs a, int T, int n_rest) {
+  constexpr int BM = 256;
+  constexpr int kStageBytes = 2 * kTileBytes;
+  __shared__ __attribute__((aligned(1024))) char smem[3 * kStageBytes];   // [stage][K,V]
+
+  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g32 = lane >> 5, l32 = lane & 31;
+  const int grp = w >> 2;
+
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int y = slot / T;
+  const int qt = T - 1 - (slot - y * T);
+  const int hr = y % a.r;
+  int rest = (y / a.r) * 8 + xcd;
+  if (rest >= n_rest) return;
+  const int NG = a.N / a.G;
+  const int gidx = rest % NG; rest /= NG;
+  const int c = rest % a.Hkv;
+  const int b = rest / a.Hkv;
+  const int h = c * a.r + hr;
+
+  const int s = shift_of_head(a, h);
+  const int split = split_of_group(a, gidx, s);
+  const int i0 = qt * BM;
+  const int qw0 = i0 + w * 32;
+  const int qrow = qw0 + l32;
+  const int jt_first = (i0 >= split ? split : 0) / BN;     // first tile any wave needs
+  const int nt = (i0 + BM - 1) / BN - jt_first + 1;        // tiles the workgroup walks
+  // this wave's own tile range, relative to jt_first
+  const int n_lo = (qw0 >= split ? split : 0) / BN - jt_first;
+  const int n_hi = (qw0 + 31) / BN - jt_first;
+  const float c2 = a.scale_log2;
+
+  const __bf16* qp = static_cast<const __bf16*>(a.q);
+  const char* kp = static_cast<const char*>(a.k);
+  const char* vp = static_cast<const char*>(a.v);
+
+  bf16x8 qf[8];
+  {
     const int tok = token_of(gidx * a.G + qrow, s, a.N);
-    a.lse[((size_t)b * a.H + h) * a.N + tok] = (st.m_run * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
+    const bf16x8* src = reinterpret_cast<const bf16x8*>(qp + ((size_t)((size_t)b * a.N + tok) * a.H + h) * 128);
+#pragma unroll
+    for (int st = 0; st < 8; ++st) qf[st] = src[2 * st + g32];
   }
+
+  // staging: wave w, pass p fills tile rows 32p + 4w .. +3 of K and of V
+  const int st_row = 4 * w + (lane >> 4);
+  const size_t kv_row_bytes = (size_t)a.Hkv * 256;
+  const uint32_t smem_base = lds_addr(smem);
+  const size_t st_goff = (size_t)st_row * kv_row_bytes + (size_t)(((lane & 15) ^ swz(st_row)) << 4);
+  auto issue_tile = [&](int n, int stage) {
+    const int tok0 = token_of(gidx * a.G + (jt_first + n) * BN, s, a.N);
+    const size_t base = ((size_t)((size_t)b * a.N + tok0) * a.Hkv + c) * 256 + st_goff;
+    const uint32_t ks = smem_base + stage * kStageBytes + 4 * w * kRowBytes;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      dma16(kp + base + (size_t)p * 32 * kv_row_bytes, ks + 32 * p * kRowBytes);
+      dma16(vp + base + (size_t)p * 32 * kv_row_bytes, ks + 32 * p * kRowBytes + kTileBytes);
+    }
+  };
+
+  LaneOffsets lo;
+  init_lane_offsets(lo, lane);
+  FwdState st;
+  st.m_run = -INFINITY;
+  st.l_run = 0.f;
+#pragma unroll
+  for (int db = 0; db < 4; ++db) st.o_acc[db] = zero16();
+  f32x16 s0, s1;       // scores of the tile whose softmax is pending
+  bf16x8 pf[4];        // probabilities of the tile whose PV product is pending
+  bf16x8 ring[4][4];   // operand fragments of steps k, k+1, k+2 (slot = step mod 4)
+
+  // ---- prologue: tiles 0 and 1 in flight, scores of tile 0
+  issue_tile(0, 0);
+  if (nt > 1) {
+    issue_tile(1, 1);
+    __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): tile 0 has landed, tile 1 may be in flight
+  } else {
+    wait_vmcnt0();
+  }
+  __syncthreads();
+  if (n_lo <= 0 && 0 <= n_hi) {
+    fwd_scores(s0, s1, qf, smem, lo, jt_first * BN, qrow, g32, jt_first * BN + BN - 1 > qw0);
+    if (grp == 0) fwd_softmax(st, s0, s1, c2, pf);
+    pp_load<0>(ring[0], smem + kTileBytes, nullptr, lo);     // first two steps of P(0) V(0)
+    pp_load<1>(ring[1], smem + kTileBytes, nullptr, lo);
+  }
+
+  int st_cur = 0, st_nxt = 1, st_free = 2;   // stages of tile n, tile n+1, and the free one
+  for (int n = 0; n < nt; ++n) {
+    wait_vmcnt0();        // this wave's part of tile n+1 has landed
+    __syncthreads();      // all of tile n+1 has landed; every wave has left tile n-1
+    if (n + 2 < nt) issue_tile(n + 2, st_free);
+    const bool act = n_lo <= n && n <= n_hi;
+    const bool act_next = n + 1 < nt && n_lo <= n + 1 && n + 1 <= n_hi;
+    const char* Vs_cur = smem + st_cur * kStageBytes + kTileBytes;
+    const char* Ks_nxt = smem + st_nxt * kStageBytes;
+    const char* Vs_nxt = Ks_nxt + kTileBytes;
+    if (grp == 1 && act) fwd_softmax(st, s0, s1, c2, pf);
+    // Every step issues the LDS reads of the step two ahead, then its own four MFMAs.
+    if (act) {
+      pp_load<2>(ring[2], Vs_cur, Ks_nxt, lo);
+      pp_mma<0>(ring[0], st, pf, qf, s0, s1);
+      __builtin_amdgcn_sched_barrier(0);
+      pp_load<3>(ring[3], Vs_cur, Ks_nxt, lo);
+      pp_mma<1>(ring[1], st, pf, qf, s0, s1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (act_next) pp_load<4>(ring[0], Vs_cur, Ks_nxt, lo);
+      pp_mma<2>(ring[2], st, pf, qf, s0, s1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (act_next) pp_load<5>(ring[1], Vs_cur, Ks_nxt, lo);
+      pp_mma<3>(ring[3], st, pf, qf, s0, s1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (act_next) {
+      if (!act) {   // this wave's first tile: nothing was prefetched
+        pp_load<4>(ring[0], Vs_cur, Ks_nxt, lo);
+        pp_load<5>(ring[1], Vs_cur, Ks_nxt, lo);
+      }
+      s0 = zero16();
+      s1 = zero16();
+      pp_load<6>(ring[2], Vs_cur, Ks_nxt, lo);
+      pp_mma<4>(ring[0], st, pf, qf, s0, s1);
+      __builtin_amdgcn_sched_barrier(0);
+      pp_load<7>(ring[3], Vs_cur, Ks_nxt, lo);
+      pp_mma<5>(ring[1], st, pf, qf, s0, s1);
+      __builtin_amdgcn_sched_barrier(0);
+      pp_load<0>(ring[0], Vs_nxt, nullptr, lo);     // first two steps of the next iteration
+      pp_mma<6>(ring[2], st, pf, qf, s0, s1);
+      __builtin_amdgcn_sched_barrier(0);
+      pp_load<1>(ring[1], Vs_nxt, nullptr, lo);
+      pp_mma<7>(ring[3], st, pf, qf, s0, s1);
+      __builtin_amdgcn_sched_barrier(0);
+      const int j0 = (jt_first + n + 1) * BN;
+      if (j0 + BN - 1 > qw0) mask_scores(s0, s1, j0, qrow, g32);
+      if (grp == 0) fwd_softmax(st, s0, s1, c2, pf);
+    }
+    const int t = st_cur; st_cur = st_nxt; st_nxt = st_free; st_free = t;
+  }
+  __syncthreads();
+  fwd_epilogue(a, st, smem + w * (32 * kRowBytes), b, h, gidx, s, qw0, c2, lane, l32, g32);
 }
 
 }  // namespace
 
 int launch_fwd_bf16(const KArgs& a, hipStream_t st) {
+  const int n_groups = a.B * a.Hkv * (a.N / a.G);
+  if (a.G % 256 == 0) {
+    const int T = a.G / 256;
+    const int blocks = 8 * T * a.r * ((n_groups + 7) / 8);
+    hipLaunchKernelGGL(fwd_bf16_pp_kernel, dim3(blocks), dim3(512), 0, st, a, T, n_groups);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+  }
   const int T = a.G / 128;
   const int n_rest = a.B * a.Hkv * (a.N / a.G);
   const int blocks = 8 * T * a.r * ((n_rest + 7) / 8);
