@@ -15,6 +15,8 @@
 // dQ: a workgroup owns 128 query rows (32 per wave, Q^T and dO^T fragments in
 //   registers) and walks the 64-key tiles up to the diagonal: S^T = K Q^T,
 //   dP^T = V dO^T, dQ^T += K^T dS^T with K^T through transposing LDS loads.
+#include <type_traits>
+
 #include "s2attn_bf16_common.h"
 #include "s2attn_device.h"
 #include "s2attn_launch.h"
@@ -198,30 +200,31 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
 
   // block -> (batch, kv head, class, group, key tile); heaviest key tiles (jt = 0) first
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int y = slot / T;
+  const int y = uni(slot / T);
   const int jt = slot - y * T;
-  int rest = y * 8 + xcd;
+  int rest = uni(y * 8 + xcd);
   if (rest >= n_rest) return;
-  const int NG = a.N / a.G;
-  const int gidx = rest % NG; rest /= NG;
-  const int cls_slot = rest % ncls; rest /= ncls;
-  const int c = rest % a.Hkv;
-  const int b = rest / a.Hkv;
+  const int NG = uni(a.N / a.G);
+  const int gidx = uni(rest % NG); rest = uni(rest / NG);
+  const int cls_slot = uni(rest % ncls); rest = uni(rest / ncls);
+  const int c = uni(rest % a.Hkv);
+  const int b = uni(rest / a.Hkv);
 
   int h_lo = c * a.r, h_hi = (c + 1) * a.r;
   const int cls = ncls == 2 ? cls_slot : (h_lo >= a.shifted_from ? 1 : 0);
   if (cls == 0) h_hi = min(h_hi, a.shifted_from); else h_lo = max(h_lo, a.shifted_from);
-  const int nheads = max(h_hi - h_lo, 0);
+  const int nheads = uni(max(h_hi - h_lo, 0));
+  h_lo = uni(h_lo);
 
-  const int s = cls ? a.shift : 0;
-  const int split = split_of_group(a, gidx, s);
+  const int s = uni(cls ? a.shift : 0);
+  const int split = uni(split_of_group(a, gidx, s));
   const int j0 = jt * 128;
   const int kw0 = j0 + 32 * w;                       // first key of this wave
   const int key = kw0 + l32;
   // query rows visible to this workgroup's keys: [j0, q_end)
-  const int q_end = (j0 + 127 < split) ? split : a.G;
-  const int it_begin = j0 / kQTileRows;
-  const int nq = (q_end - j0 + kQTileRows - 1) / kQTileRows;
+  const int q_end = uni((j0 + 127 < split) ? split : a.G);
+  const int it_begin = uni(j0 / kQTileRows);
+  const int nq = uni((q_end - j0 + kQTileRows - 1) / kQTileRows);
   const int n_iter = nheads * nq;
   const float c2 = a.scale_log2;
 
@@ -247,8 +250,8 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
   const int st_row = 4 * w + (lane >> 4);
   const size_t st_goff = (size_t)st_row * q_row_bytes + (size_t)(((lane & 15) ^ swz(st_row)) << 4);
   auto issue_tile = [&](int n, int stage) {
-    const int h = h_lo + n / nq;
-    const int q0 = (it_begin + n % nq) * kQTileRows;
+    const int h = h_lo + uni(n / nq);
+    const int q0 = (it_begin + uni(n % nq)) * kQTileRows;
     const uint32_t qs = smem_base + stage * 2 * kQTileBytes + 4 * w * kRowBytes;
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
@@ -280,7 +283,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
     wait_vmcnt0();
     __syncthreads();
     if (n + 1 < n_iter) issue_tile(n + 1, stage ^ 1);
-    const int q0 = (it_begin + n % nq) * kQTileRows;
+    const int q0 = (it_begin + uni(n % nq)) * kQTileRows;
     DkdvTile t;
     t.Qs = smem + stage * 2 * kQTileBytes;
     t.dOs = t.Qs + kQTileBytes;
@@ -343,26 +346,44 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
 constexpr int BN = 64;                       // keys per tile
 constexpr int kTileBytes = BN * kRowBytes;   // 16 KB
 
-// dS^T of the 32 keys starting at tile row ROW0, as two packed B operands.
-template <int ROW0>
-__device__ __forceinline__ void dq_scores(bf16x8& ds_lo, bf16x8& ds_hi, const bf16x8 (&qf)[8], const bf16x8 (&dof)[8],
-                                          const char* Ks, const char* Vs, const LaneOffsets& lo, int j0, int qrow,
-                                          float c2, float lse2, float delta, int g32, bool masked) {
-  f32x16 sa = zero16(), pa = zero16();
+// One 64-key tile of the dQ kernel as 12 steps of 4 MFMAs, each fed by 4 fragments:
+//   steps 0-3 / 4-7: S^T and dP^T of key block 0 / 1 over d = 32j .. 32j+31
+//   steps 8-11:      dQ^T += K^T dS^T for keys 16k .. 16k+15
+// Every step first issues the LDS reads of the next step into the other fragment buffer
+// (also across the exp/multiply sections), then runs its own four MFMAs.
+template <int STEP>
+__device__ __forceinline__ void dq_load(bf16x8 (&buf)[4], const char* Ks, const char* Vs, const LaneOffsets& lo) {
+  if constexpr (STEP < 8) {
+    constexpr int ROW0 = 32 * (STEP / 4), J = STEP % 4;
+    buf[0] = frag_rm<ROW0>(Ks, lo, 2 * J);
+    buf[1] = frag_rm<ROW0>(Vs, lo, 2 * J);
+    buf[2] = frag_rm<ROW0>(Ks, lo, 2 * J + 1);
+    buf[3] = frag_rm<ROW0>(Vs, lo, 2 * J + 1);
+  } else {
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    bf16x8 kr[4], vr[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      kr[i] = frag_rm<ROW0>(Ks, lo, 4 * half + i);
-      vr[i] = frag_rm<ROW0>(Vs, lo, 4 * half + i);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      sa = mfma32(kr[i], qf[4 * half + i], sa);
-      pa = mfma32(vr[i], dof[4 * half + i], pa);
-    }
+    for (int db = 0; db < 4; ++db) buf[db] = frag_tr<16 * (STEP - 8)>(Ks, lo, db);
   }
+}
+
+template <int STEP>
+__device__ __forceinline__ void dq_mma(const bf16x8 (&buf)[4], const bf16x8 (&qf)[8], const bf16x8 (&dof)[8],
+                                       f32x16& sa, f32x16& pa, const bf16x8 (&dsf)[4], f32x16 (&dq_acc)[4]) {
+  if constexpr (STEP < 8) {
+    constexpr int J = STEP % 4;
+    sa = mfma32(buf[0], qf[2 * J], sa);
+    pa = mfma32(buf[1], dof[2 * J], pa);
+    sa = mfma32(buf[2], qf[2 * J + 1], sa);
+    pa = mfma32(buf[3], dof[2 * J + 1], pa);
+  } else {
+#pragma unroll
+    for (int db = 0; db < 4; ++db) dq_acc[db] = mfma32(buf[db], dsf[STEP - 8], dq_acc[db]);
+  }
+}
+
+// dS^T = P^T * (dP^T - delta) of one 32-key block, packed as two B operands.
+template <int ROW0>
+__device__ __forceinline__ void dq_ds(f32x16& sa, const f32x16& pa, bf16x8& ds_lo, bf16x8& ds_hi, int j0, int qrow,
+                                      float c2, float lse2, float delta, int g32, bool masked) {
   if (masked) {   // wave-uniform: exp2(-inf) = 0 removes keys after the query
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -376,26 +397,36 @@ __device__ __forceinline__ void dq_scores(bf16x8& ds_lo, bf16x8& ds_hi, const bf
   ds_hi = pack8(sa[8], sa[9], sa[10], sa[11], sa[12], sa[13], sa[14], sa[15]);
 }
 
-// dQ^T += K^T dS^T for the 16 keys starting at tile row KROW0.
-template <int KROW0>
-__device__ __forceinline__ void dq_step(f32x16 (&dq_acc)[4], const char* Ks, const LaneOffsets& lo, bf16x8 dsf) {
-  bf16x8 kt[4];
-#pragma unroll
-  for (int db = 0; db < 4; ++db) kt[db] = frag_tr<KROW0>(Ks, lo, db);
-#pragma unroll
-  for (int db = 0; db < 4; ++db) dq_acc[db] = mfma32(kt[db], dsf, dq_acc[db]);
-}
-
 __device__ __forceinline__ void dq_tile(f32x16 (&dq_acc)[4], const bf16x8 (&qf)[8], const bf16x8 (&dof)[8],
                                         const char* Ks, const char* Vs, const LaneOffsets& lo, int j0,
                                         int qrow, float c2, float lse2, float delta, int g32, bool masked) {
-  bf16x8 dsf[4];
-  dq_scores<0>(dsf[0], dsf[1], qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32, masked);
-  dq_scores<32>(dsf[2], dsf[3], qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32, masked);
-  dq_step<0>(dq_acc, Ks, lo, dsf[0]);
-  dq_step<16>(dq_acc, Ks, lo, dsf[1]);
-  dq_step<32>(dq_acc, Ks, lo, dsf[2]);
-  dq_step<48>(dq_acc, Ks, lo, dsf[3]);
+#define S2_DQ_STEP(N, CUR, NXT)                                   \
+  dq_load<N + 1>(NXT, Ks, Vs, lo);                                \
+  dq_mma<N>(CUR, qf, dof, sa, pa, dsf, dq_acc);                   \
+  __builtin_amdgcn_sched_barrier(0)
+  bf16x8 fa[4], fb[4], dsf[4];
+  f32x16 sa = zero16(), pa = zero16();
+  dq_load<0>(fa, Ks, Vs, lo);
+  __builtin_amdgcn_sched_barrier(0);
+  S2_DQ_STEP(0, fa, fb);
+  S2_DQ_STEP(1, fb, fa);
+  S2_DQ_STEP(2, fa, fb);
+  S2_DQ_STEP(3, fb, fa);            // loads step 4 (block 1) before the vector section
+  dq_ds<0>(sa, pa, dsf[0], dsf[1], j0, qrow, c2, lse2, delta, g32, masked);
+  sa = zero16();
+  pa = zero16();
+  __builtin_amdgcn_sched_barrier(0);
+  S2_DQ_STEP(4, fa, fb);
+  S2_DQ_STEP(5, fb, fa);
+  S2_DQ_STEP(6, fa, fb);
+  S2_DQ_STEP(7, fb, fa);            // loads step 8 (first K^T fragments)
+  dq_ds<32>(sa, pa, dsf[2], dsf[3], j0, qrow, c2, lse2, delta, g32, masked);
+  __builtin_amdgcn_sched_barrier(0);
+  S2_DQ_STEP(8, fa, fb);
+  S2_DQ_STEP(9, fb, fa);
+  S2_DQ_STEP(10, fa, fb);
+  dq_mma<11>(fb, qf, dof, sa, pa, dsf, dq_acc);
+#undef S2_DQ_STEP
 }
 
 __global__ void __launch_bounds__(256, 2)
@@ -407,24 +438,24 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
   const int g32 = lane >> 5, l32 = lane & 31;
 
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int y = slot / T;
+  const int y = uni(slot / T);
   const int qt = T - 1 - (slot - y * T);
-  const int hr = y % a.r;
-  int rest = (y / a.r) * 8 + xcd;
+  const int hr = uni(y % a.r);
+  int rest = uni(uni(y / a.r) * 8 + xcd);
   if (rest >= n_rest) return;
-  const int NG = a.N / a.G;
-  const int gidx = rest % NG; rest /= NG;
-  const int c = rest % a.Hkv;
-  const int b = rest / a.Hkv;
+  const int NG = uni(a.N / a.G);
+  const int gidx = uni(rest % NG); rest = uni(rest / NG);
+  const int c = uni(rest % a.Hkv);
+  const int b = uni(rest / a.Hkv);
   const int h = c * a.r + hr;
 
-  const int s = shift_of_head(a, h);
-  const int split = split_of_group(a, gidx, s);
+  const int s = uni(shift_of_head(a, h));
+  const int split = uni(split_of_group(a, gidx, s));
   const int i0 = qt * BM;
   const int qw0 = i0 + w * 32;
   const int qrow = qw0 + l32;
-  const int lo_w = qw0 >= split ? split : 0;
-  const int jt_first = (i0 >= split ? split : 0) / BN;
+  const int lo_w = uni(qw0 >= split ? split : 0);
+  const int jt_first = uni((i0 >= split ? split : 0) / BN);
   const int jt_diag = i0 / BN;
   const float c2 = a.scale_log2;
 
@@ -468,17 +499,23 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
 
   issue_tile(jt_first, 0);
   const int n_tiles = jt_diag + 2 - jt_first;
-  for (int n = 0; n < n_tiles; ++n) {
+  // The stage is a compile-time constant of the body (the loop is unrolled by the number
+  // of stages), so every LDS read is lane offset + immediate.
+  auto body = [&](auto stage_c, int n) {
+    constexpr int STAGE = decltype(stage_c)::value;
     const int jt = jt_first + n;
-    const int stage = n & 1;
     wait_vmcnt0();
     __syncthreads();
-    if (n + 1 < n_tiles) issue_tile(jt + 1, stage ^ 1);
+    if (n + 1 < n_tiles) issue_tile(jt + 1, STAGE ^ 1);
     const int j0 = jt * BN;
-    const char* Ks = smem + stage * 2 * kTileBytes;
+    const char* Ks = smem + STAGE * 2 * kTileBytes;
     const char* Vs = Ks + kTileBytes;
-    if (j0 > qw0 + 31 || j0 + BN - 1 < lo_w) continue;   // wholly outside this wave's visible keys
+    if (j0 > qw0 + 31 || j0 + BN - 1 < lo_w) return;   // wholly outside this wave's visible keys
     dq_tile(dq_acc, qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32, j0 + BN - 1 > qw0);
+  };
+  for (int n = 0; n < n_tiles; n += 2) {
+    body(std::integral_constant<int, 0>{}, n);
+    if (n + 1 < n_tiles) body(std::integral_constant<int, 1>{}, n + 1);
   }
   __syncthreads();
 

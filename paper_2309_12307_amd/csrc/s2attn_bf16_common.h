@@ -101,6 +101,10 @@ __device__ __forceinline__ void dma4(const void* g, uint32_t lds_base) {
                :: "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(g) : "memory", "m0");
 }
 
+// Marks a wave-uniform value that was computed with vector instructions (integer division has
+// no scalar form) so that it lives in a scalar register and loops/branches on it are scalar.
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)S2_LDS(const char, p));
 }

@@ -171,24 +171,24 @@ fwd_bf16_kernel(KArgs a, int T, int n_rest) {
   // all query tiles (heaviest first) of a triple back to back, so that the K/V of a
   // group stay in that XCD's L2 while they are being re-read.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int y = slot / T;
+  const int y = uni(slot / T);
   const int qt = T - 1 - (slot - y * T);
-  const int hr = y % a.r;
-  int rest = (y / a.r) * 8 + xcd;
+  const int hr = uni(y % a.r);
+  int rest = uni(uni(y / a.r) * 8 + xcd);
   if (rest >= n_rest) return;
-  const int NG = a.N / a.G;
-  const int gidx = rest % NG; rest /= NG;
-  const int c = rest % a.Hkv;
-  const int b = rest / a.Hkv;
+  const int NG = uni(a.N / a.G);
+  const int gidx = uni(rest % NG); rest = uni(rest / NG);
+  const int c = uni(rest % a.Hkv);
+  const int b = uni(rest / a.Hkv);
   const int h = c * a.r + hr;
 
-  const int s = shift_of_head(a, h);
-  const int split = split_of_group(a, gidx, s);
+  const int s = uni(shift_of_head(a, h));
+  const int split = uni(split_of_group(a, gidx, s));
   const int i0 = qt * BM;
   const int qw0 = i0 + w * 32;                      // first query row of this wave
   const int qrow = qw0 + l32;
-  const int lo_w = qw0 >= split ? split : 0;        // first key visible to this wave
-  const int jt_first = (i0 >= split ? split : 0) / BN;
+  const int lo_w = uni(qw0 >= split ? split : 0);        // first key visible to this wave
+  const int jt_first = uni((i0 >= split ? split : 0) / BN);
   const int jt_diag = i0 / BN;                      // tiles jt_diag, jt_diag + 1 touch the diagonal
   const float c2 = a.scale_log2;
 
@@ -319,27 +319,27 @@ fwd_bf16_pp_kernel(KArgs a, int T, int n_rest) {
   const int grp = w >> 2;
 
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int y = slot / T;
+  const int y = uni(slot / T);
   const int qt = T - 1 - (slot - y * T);
-  const int hr = y % a.r;
-  int rest = (y / a.r) * 8 + xcd;
+  const int hr = uni(y % a.r);
+  int rest = uni(uni(y / a.r) * 8 + xcd);
   if (rest >= n_rest) return;
-  const int NG = a.N / a.G;
-  const int gidx = rest % NG; rest /= NG;
-  const int c = rest % a.Hkv;
-  const int b = rest / a.Hkv;
+  const int NG = uni(a.N / a.G);
+  const int gidx = uni(rest % NG); rest = uni(rest / NG);
+  const int c = uni(rest % a.Hkv);
+  const int b = uni(rest / a.Hkv);
   const int h = c * a.r + hr;
 
-  const int s = shift_of_head(a, h);
-  const int split = split_of_group(a, gidx, s);
+  const int s = uni(shift_of_head(a, h));
+  const int split = uni(split_of_group(a, gidx, s));
   const int i0 = qt * BM;
   const int qw0 = i0 + w * 32;
   const int qrow = qw0 + l32;
-  const int jt_first = (i0 >= split ? split : 0) / BN;     // first tile any wave needs
+  const int jt_first = uni((i0 >= split ? split : 0) / BN);     // first tile any wave needs
   const int nt = (i0 + BM - 1) / BN - jt_first + 1;        // tiles the workgroup walks
   // this wave's own tile range, relative to jt_first
-  const int n_lo = (qw0 >= split ? split : 0) / BN - jt_first;
-  const int n_hi = (qw0 + 31) / BN - jt_first;
+  const int n_lo = uni((qw0 >= split ? split : 0) / BN - jt_first);
+  const int n_hi = uni((qw0 + 31) / BN - jt_first);
   const float c2 = a.scale_log2;
 
   const __bf16* qp = static_cast<const __bf16*>(a.q);
