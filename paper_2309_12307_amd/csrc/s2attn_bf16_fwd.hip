@@ -81,10 +81,14 @@ __device__ __forceinline__ void fwd_scores(f32x16& s0, f32x16& s1, const bf16x8 
 // Online softmax of the tile: updates the running maximum lazily, accumulates the row
 // sum and packs the probabilities as the four 16-key B operands of the PV product.
 __device__ __forceinline__ void fwd_softmax(FwdState& st, f32x16& s0, f32x16& s1, float c2, bf16x8 (&pf)[4]) {
-  float mx = fmaxf(s0[0], s1[0]);
+  // two independent three-input maximum chains
+  float ma = fmaxf(s0[0], s0[1]), mb = fmaxf(s1[0], s1[1]);
 #pragma unroll
-  for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s0[v], s1[v]));
-  mx = max_halves(mx);
+  for (int v = 2; v < 16; v += 2) {
+    ma = fmaxf(fmaxf(ma, s0[v]), s0[v + 1]);
+    mb = fmaxf(fmaxf(mb, s1[v]), s1[v + 1]);
+  }
+  const float mx = max_halves(fmaxf(ma, mb));
   if (__builtin_amdgcn_ballot_w64(mx * c2 > st.m_run * c2 + kRescaleThreshold) != 0) {
     const float m_new = fmaxf(st.m_run, mx);
     const float alpha = __builtin_amdgcn_exp2f((st.m_run - m_new) * c2);
@@ -96,14 +100,15 @@ __device__ __forceinline__ void fwd_softmax(FwdState& st, f32x16& s0, f32x16& s1
       for (int v = 0; v < 16; ++v) st.o_acc[db][v] *= alpha;
   }
   const float mc = st.m_run * c2;
-  float rs = 0.f;
+  float ra = 0.f, rb = 0.f;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     s0[v] = __builtin_amdgcn_exp2f(fmaf(s0[v], c2, -mc));
     s1[v] = __builtin_amdgcn_exp2f(fmaf(s1[v], c2, -mc));
-    rs += s0[v] + s1[v];
+    ra += s0[v];
+    rb += s1[v];
   }
-  st.l_run += rs;
+  st.l_run += ra + rb;
   pf[0] = pack8(s0[0], s0[1], s0[2], s0[3], s0[4], s0[5], s0[6], s0[7]);
   pf[1] = pack8(s0[8], s0[9], s0[10], s0[11], s0[12], s0[13], s0[14], s0[15]);
   pf[2] = pack8(s1[0], s1[1], s1[2], s1[3], s1[4], s1[5], s1[6], s1[7]);
