@@ -186,4 +186,17 @@ __device__ __forceinline__ f32x16 zero16() {
   return z;
 }
 
+// Transposes a wave's 32 x 128 accumulator block (rows lane-indexed, columns
+// register-indexed) through its private 8 KB LDS region.
+__device__ __forceinline__ void acc_to_lds(char* region, const f32x16 (&acc)[4], float mul, int l32, int g32) {
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int vv = 0; vv < 4; ++vv) {
+      const bf16x4 pk = pack4(acc[db][4 * vv] * mul, acc[db][4 * vv + 1] * mul,
+                              acc[db][4 * vv + 2] * mul, acc[db][4 * vv + 3] * mul);
+      *reinterpret_cast<bf16x4*>(region + tile_off(l32, 4 * db + vv) + 8 * g32) = pk;
+    }
+}
+
 }  // namespace s2
