@@ -52,7 +52,8 @@ enum {
   S2ATTN_ERR_DTYPE = -9,       /* unknown dtype / rule / variant value */
   S2ATTN_ERR_DEVICE = -10,     /* current device is not gfx950 */
   S2ATTN_ERR_LAUNCH = -11,     /* HIP reported a launch error */
-  S2ATTN_ERR_TOO_LARGE = -12   /* tensor too large for the index arithmetic, or over a fixed limit */
+  S2ATTN_ERR_TOO_LARGE = -12,  /* tensor too large for the index arithmetic, or over a fixed limit */
+  S2ATTN_ERR_STRIDE = -13      /* a stride is negative, misaligned or smaller than the extent it spans */
 };
 
 enum { S2ATTN_BF16 = 0, S2ATTN_F32 = 1 };
@@ -91,6 +92,13 @@ typedef struct s2attn_params {
   int shift_rule;     /* S2ATTN_SHIFT_* */
   int wrap_variant;   /* S2ATTN_WRAP_* */
   float scale;        /* softmax scale; <= 0 means 1/sqrt(D) */
+  /* Optional element strides {batch, token, head} of q, k, v, dq, dk, dv (the head-dim
+   * axis is always contiguous).  All three zero = contiguous.  Lets the three slices of a
+   * packed (B, N, 3, H, D) projection (Algorithm 1's qkv) be passed without a split copy:
+   * {N*3*H*D, 3*H*D, D} with pointers offset by 0, H*D and 2*H*D elements.  Every stride
+   * must be a multiple of 8 elements (bf16) or 4 (fp32); o, dout, lse stay contiguous. */
+  long long q_strides[3], k_strides[3], v_strides[3];
+  long long dq_strides[3], dk_strides[3], dv_strides[3];
 } s2attn_params;
 
 /* Pure host check of a parameter block (pointers, alignment, shapes, workspace

@@ -34,6 +34,9 @@ class S2AttnParams(ctypes.Structure):
         ("Hkv", ctypes.c_int), ("D", ctypes.c_int), ("G", ctypes.c_int),
         ("dtype", ctypes.c_int), ("shift", ctypes.c_int), ("shift_rule", ctypes.c_int),
         ("wrap_variant", ctypes.c_int), ("scale", ctypes.c_float),
+        ("q_strides", ctypes.c_longlong * 3), ("k_strides", ctypes.c_longlong * 3),
+        ("v_strides", ctypes.c_longlong * 3), ("dq_strides", ctypes.c_longlong * 3),
+        ("dk_strides", ctypes.c_longlong * 3), ("dv_strides", ctypes.c_longlong * 3),
     ]
 
 
@@ -137,7 +140,9 @@ def effective_flops(B, N, H, D, G, which: int = 2) -> float:
 
 def make_params(q, k, v, o, lse, G, dout=None, dq=None, dk=None, dv=None, workspace=None,
                 shift=-1, shift_rule=SHIFT_SECOND_HALF, wrap_variant=WRAP_JOINT, scale=0.0,
-                dtype=None, dims=None) -> S2AttnParams:
+                dtype=None, dims=None, strided=False) -> S2AttnParams:
+    """strided=True takes the {batch, token, head} strides of q, k, v (and dq, dk, dv) from
+    the tensors themselves, so views into a packed (B, N, 3, H, D) tensor can be passed."""
     if dims is None:
         B, N, H, Hkv, D = _dims(q, k)
     else:
@@ -150,6 +155,13 @@ def make_params(q, k, v, o, lse, G, dout=None, dq=None, dk=None, dv=None, worksp
     p.B, p.N, p.H, p.Hkv, p.D, p.G = B, N, H, Hkv, D, G
     p.dtype = _dtype_code(q) if dtype is None else dtype
     p.shift, p.shift_rule, p.wrap_variant, p.scale = shift, shift_rule, wrap_variant, scale
+    if strided:
+        for name, t in (("q", q), ("k", k), ("v", v), ("dq", dq), ("dk", dk), ("dv", dv)):
+            if t is None or isinstance(t, int):
+                continue
+            if t.stride(3) != 1:
+                raise ValueError("the head-dim axis must be contiguous")
+            setattr(p, name + "_strides", (ctypes.c_longlong * 3)(t.stride(0), t.stride(1), t.stride(2)))
     return p
 
 

@@ -45,6 +45,16 @@ size_t workspace_bytes_for(int B, int N, int H, int Hkv, int D, bool mixed) {
   return w;
 }
 
+bool strides_ok(const long long (&st)[3], int B, int heads, int D, int align) {
+  if (st[0] == 0 && st[1] == 0 && st[2] == 0) return true;
+  for (long long x : st)
+    if (x < 0 || x % align != 0) return false;
+  if (st[2] < D && heads > 1) return false;
+  if (st[1] < D) return false;
+  if (st[0] < D && B > 1) return false;
+  return true;
+}
+
 int check_common(const s2attn_params* p, int backward) {
   if (!p) return S2ATTN_ERR_NULL;
   if (p->dtype != S2ATTN_BF16 && p->dtype != S2ATTN_F32) return S2ATTN_ERR_DTYPE;
@@ -65,6 +75,14 @@ int check_common(const s2attn_params* p, int backward) {
   if ((long long)p->B * p->H * 2 > 65535 || (long long)p->N / p->G > 65535) return S2ATTN_ERR_TOO_LARGE;
   if ((double)p->B * p->N * p->H * p->D > 9.0e18 / 4) return S2ATTN_ERR_TOO_LARGE;
 
+  const int align = p->dtype == S2ATTN_F32 ? 4 : 8;
+  if (!strides_ok(p->q_strides, p->B, p->H, p->D, align) || !strides_ok(p->k_strides, p->B, p->Hkv, p->D, align) ||
+      !strides_ok(p->v_strides, p->B, p->Hkv, p->D, align))
+    return S2ATTN_ERR_STRIDE;
+  if (backward && (!strides_ok(p->dq_strides, p->B, p->H, p->D, align) ||
+                   !strides_ok(p->dk_strides, p->B, p->Hkv, p->D, align) ||
+                   !strides_ok(p->dv_strides, p->B, p->Hkv, p->D, align)))
+    return S2ATTN_ERR_STRIDE;
   const void* need_fwd[] = {p->q, p->k, p->v, p->o, p->lse};
   for (const void* x : need_fwd) {
     if (!x) return S2ATTN_ERR_NULL;
@@ -100,6 +118,17 @@ int check_device() {
   return state == 1 ? S2ATTN_OK : S2ATTN_ERR_DEVICE;
 }
 
+// Strides of a tensor with `heads` heads: the caller's, or contiguous (B, N, heads, D) when all zero.
+s2::TStride resolve_strides(const long long (&st)[3], int N, int heads, int D) {
+  s2::TStride r;
+  if (st[0] == 0 && st[1] == 0 && st[2] == 0) {
+    r.b = (long long)N * heads * D; r.t = (long long)heads * D; r.h = D;
+  } else {
+    r.b = st[0]; r.t = st[1]; r.h = st[2];
+  }
+  return r;
+}
+
 s2::KArgs make_kargs(const s2attn_params* p) {
   s2::KArgs a;
   std::memset(&a, 0, sizeof(a));
@@ -107,6 +136,14 @@ s2::KArgs make_kargs(const s2attn_params* p) {
   a.dout = p->dout; a.dq = p->dq; a.dk = p->dk; a.dv = p->dv;
   a.B = p->B; a.N = p->N; a.H = p->H; a.Hkv = p->Hkv; a.D = p->D; a.G = p->G;
   a.r = p->H / p->Hkv;
+  a.sq = resolve_strides(p->q_strides, p->N, p->H, p->D);
+  a.sk = resolve_strides(p->k_strides, p->N, p->Hkv, p->D);
+  a.sv = resolve_strides(p->v_strides, p->N, p->Hkv, p->D);
+  a.sdq = resolve_strides(p->dq_strides, p->N, p->H, p->D);
+  a.sdk = resolve_strides(p->dk_strides, p->N, p->Hkv, p->D);
+  a.sdv = resolve_strides(p->dv_strides, p->N, p->Hkv, p->D);
+  const long long zero3[3] = {0, 0, 0};
+  a.so = resolve_strides(zero3, p->N, p->H, p->D);
   a.shift = resolved_shift(p);
   a.shifted_from = shifted_from(p->shift_rule, p->H, a.shift);
   a.split = (p->wrap_variant == S2ATTN_WRAP_SPLIT && a.shift > 0) ? p->G - a.shift : p->G;
@@ -237,6 +274,7 @@ const char* s2attn_strerror(int code) {
     case S2ATTN_ERR_DEVICE: return "current device is not gfx950 (MI355X)";
     case S2ATTN_ERR_LAUNCH: return "HIP kernel launch failed";
     case S2ATTN_ERR_TOO_LARGE: return "problem too large for the launch grid or index arithmetic";
+    case S2ATTN_ERR_STRIDE: return "a stride is negative, misaligned or smaller than the extent it spans";
     default: return "unknown s2attn error code";
   }
 }

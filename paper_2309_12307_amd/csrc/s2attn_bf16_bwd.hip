@@ -222,9 +222,8 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
   bf16x8 kf[8], vf[8];
   {
     const int tok = token_of(gidx * a.G + key, s, a.N);
-    const size_t off = ((size_t)((size_t)b * a.N + tok) * a.Hkv + c) * 128;
-    const bf16x8* ksrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.k) + off);
-    const bf16x8* vsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.v) + off);
+    const bf16x8* ksrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.k) + row_off(a.sk, b, tok, c));
+    const bf16x8* vsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.v) + row_off(a.sv, b, tok, c));
 #pragma unroll
     for (int st = 0; st < 8; ++st) { kf[st] = ksrc[2 * st + g32]; vf[st] = vsrc[2 * st + g32]; }
   }
@@ -233,9 +232,9 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
   // tile are one contiguous token run (shift and G are multiples of 64).
   const uint32_t smem_base = lds_addr(smem);
   const uint32_t rows_base = lds_addr(rows_s);
-  const size_t q_row_bytes = (size_t)a.H * 256;
+  const size_t q_row_bytes = (size_t)a.sq.t * 2, do_row_bytes = (size_t)a.so.t * 2;
   const int st_row = 4 * w + (lane >> 4);
-  const size_t st_goff = (size_t)st_row * q_row_bytes + (size_t)(((lane & 15) ^ swz(st_row)) << 4);
+  const size_t st_chunk = (size_t)(((lane & 15) ^ swz(st_row)) << 4);
   auto issue_tile = [&](int n, int stage) {
     const int h = h_lo + uni(n / nq);
     const int q0 = (it_begin + uni(n % nq)) * kQTileRows;
@@ -243,12 +242,12 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
       const int tok0 = token_of(gidx * a.G + q0 + 64 * hf, s, a.N);
-      const size_t base = ((size_t)((size_t)b * a.N + tok0) * a.H + h) * 256;
+      const size_t qbase = row_off(a.sq, b, tok0 + st_row, h) * 2 + st_chunk;
+      const size_t dobase = row_off(a.so, b, tok0 + st_row, h) * 2 + st_chunk;
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
-        const size_t go = base + st_goff + (size_t)p * 16 * q_row_bytes;
-        dma16(qp + go, qs + (64 * hf + 16 * p) * kRowBytes);
-        dma16(dop + go, qs + (64 * hf + 16 * p) * kRowBytes + kQTileBytes);
+        dma16(qp + qbase + (size_t)p * 16 * q_row_bytes, qs + (64 * hf + 16 * p) * kRowBytes);
+        dma16(dop + dobase + (size_t)p * 16 * do_row_bytes, qs + (64 * hf + 16 * p) * kRowBytes + kQTileBytes);
       }
       if (w == hf) {   // wave 0 / 1: lse and delta of rows 64*hf .. +63
         const size_t ro = ((size_t)b * a.H + h) * a.N + tok0 + lane;
@@ -296,7 +295,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
     float* dk_out = a.dkv_partial + (size_t)cls * kv_elems;
     float* dv_out = a.dkv_partial + (size_t)(2 + cls) * kv_elems;
     const int tok = token_of(gidx * a.G + key, s, a.N);
-    const size_t base = ((size_t)((size_t)b * a.N + tok) * a.Hkv + c) * 128;
+    const size_t base = ((size_t)((size_t)b * a.N + tok) * a.Hkv + c) * 128;   // partials are contiguous
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -321,9 +320,10 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
     const int tok = token_of(gidx * a.G + kw0 + row, s, a.N);
-    const size_t off = ((size_t)((size_t)b * a.N + tok) * a.Hkv + c) * 128 + ch * 8;
-    *reinterpret_cast<uint4*>(dkp + off) = *reinterpret_cast<const uint4*>(rk + tile_off(row, ch));
-    *reinterpret_cast<uint4*>(dvp + off) = *reinterpret_cast<const uint4*>(rv + tile_off(row, ch));
+    *reinterpret_cast<uint4*>(dkp + row_off(a.sdk, b, tok, c) + ch * 8) =
+        *reinterpret_cast<const uint4*>(rk + tile_off(row, ch));
+    *reinterpret_cast<uint4*>(dvp + row_off(a.sdv, b, tok, c) + ch * 8) =
+        *reinterpret_cast<const uint4*>(rv + tile_off(row, ch));
   }
 }
 
@@ -453,9 +453,8 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
   float lse2, delta;
   {
     const int tok = token_of(gidx * a.G + qrow, s, a.N);
-    const size_t off = ((size_t)((size_t)b * a.N + tok) * a.H + h) * 128;
-    const bf16x8* qsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.q) + off);
-    const bf16x8* dsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.dout) + off);
+    const bf16x8* qsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.q) + row_off(a.sq, b, tok, h));
+    const bf16x8* dsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.dout) + row_off(a.so, b, tok, h));
 #pragma unroll
     for (int st = 0; st < 8; ++st) { qf[st] = qsrc[2 * st + g32]; dof[st] = dsrc[2 * st + g32]; }
     const size_t ro = ((size_t)b * a.H + h) * a.N + tok;
@@ -464,17 +463,18 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
   }
 
   const uint32_t smem_base = lds_addr(smem);
-  const size_t kv_row_bytes = (size_t)a.Hkv * 256;
+  const size_t k_row_bytes = (size_t)a.sk.t * 2, v_row_bytes = (size_t)a.sv.t * 2;
   const int st_row = 4 * w + (lane >> 4);
-  const size_t st_goff = (size_t)st_row * kv_row_bytes + (size_t)(((lane & 15) ^ swz(st_row)) << 4);
+  const size_t st_chunk = (size_t)(((lane & 15) ^ swz(st_row)) << 4);
   auto issue_tile = [&](int jt, int stage) {
     const int tok0 = token_of(gidx * a.G + jt * BN, s, a.N);
-    const size_t base = ((size_t)((size_t)b * a.N + tok0) * a.Hkv + c) * 256 + st_goff;
+    const size_t kbase = row_off(a.sk, b, tok0 + st_row, c) * 2 + st_chunk;
+    const size_t vbase = row_off(a.sv, b, tok0 + st_row, c) * 2 + st_chunk;
     const uint32_t ks = smem_base + stage * 2 * kTileBytes + 4 * w * kRowBytes;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      dma16(kp + base + (size_t)p * 16 * kv_row_bytes, ks + 16 * p * kRowBytes);
-      dma16(vp + base + (size_t)p * 16 * kv_row_bytes, ks + 16 * p * kRowBytes + kTileBytes);
+      dma16(kp + kbase + (size_t)p * 16 * k_row_bytes, ks + 16 * p * kRowBytes);
+      dma16(vp + vbase + (size_t)p * 16 * v_row_bytes, ks + 16 * p * kRowBytes + kTileBytes);
     }
   };
 
@@ -514,7 +514,7 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
     const int tok = token_of(gidx * a.G + qw0 + row, s, a.N);
-    *reinterpret_cast<uint4*>(dqp + ((size_t)((size_t)b * a.N + tok) * a.H + h) * 128 + ch * 8) =
+    *reinterpret_cast<uint4*>(dqp + row_off(a.sdq, b, tok, h) + ch * 8) =
         *reinterpret_cast<const uint4*>(region + tile_off(row, ch));
   }
 }

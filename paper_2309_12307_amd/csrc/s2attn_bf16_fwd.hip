@@ -154,7 +154,7 @@ __device__ __forceinline__ void fwd_epilogue(const KArgs& a, FwdState& st, char*
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
     const uint4 val = *reinterpret_cast<const uint4*>(Os + tile_off(row, ch));
     const int tok = token_of(gidx * a.G + qw0 + row, s, a.N);
-    *reinterpret_cast<uint4*>(op + ((size_t)((size_t)b * a.N + tok) * a.H + h) * 128 + ch * 8) = val;
+    *reinterpret_cast<uint4*>(op + row_off(a.so, b, tok, h) + ch * 8) = val;
   }
   if (g32 == 0) {
     const int tok = token_of(gidx * a.G + qw0 + l32, s, a.N);
@@ -205,7 +205,7 @@ fwd_bf16_kernel(KArgs a, int T, int n_rest) {
   bf16x8 qf[8];
   {
     const int tok = token_of(gidx * a.G + qrow, s, a.N);
-    const bf16x8* src = reinterpret_cast<const bf16x8*>(qp + ((size_t)((size_t)b * a.N + tok) * a.H + h) * 128);
+    const bf16x8* src = reinterpret_cast<const bf16x8*>(qp + row_off(a.sq, b, tok, h));
 #pragma unroll
     for (int st = 0; st < 8; ++st) qf[st] = src[2 * st + g32];
   }
@@ -214,22 +214,18 @@ fwd_bf16_kernel(KArgs a, int T, int n_rest) {
   // (1 KB contiguous in LDS); lane i lands on physical chunk i%16 of row i/16 and
   // therefore fetches the logical chunk that the swizzle places there.
   const int st_row = 4 * w + (lane >> 4);
-  const size_t kv_row_bytes = (size_t)a.Hkv * 256;
+  const size_t k_row_bytes = (size_t)a.sk.t * 2, v_row_bytes = (size_t)a.sv.t * 2;
   const uint32_t smem_base = lds_addr(smem);
-  size_t st_goff[4];
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int row = 16 * p + st_row;
-    st_goff[p] = (size_t)row * kv_row_bytes + (size_t)(((lane & 15) ^ swz(row)) << 4);
-  }
+  const size_t st_chunk = (size_t)(((lane & 15) ^ swz(st_row)) << 4);
   auto issue_tile = [&](int jt, int stage) {
     const int tok0 = token_of(gidx * a.G + jt * BN, s, a.N);   // a tile never straddles the wrap
-    const size_t base = ((size_t)((size_t)b * a.N + tok0) * a.Hkv + c) * 256;
+    const size_t kbase = row_off(a.sk, b, tok0 + st_row, c) * 2 + st_chunk;
+    const size_t vbase = row_off(a.sv, b, tok0 + st_row, c) * 2 + st_chunk;
     const uint32_t ks = smem_base + stage * 2 * kTileBytes + 4 * w * kRowBytes;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      dma16(kp + base + st_goff[p], ks + 16 * p * kRowBytes);
-      dma16(vp + base + st_goff[p], ks + 16 * p * kRowBytes + kTileBytes);
+      dma16(kp + kbase + (size_t)p * 16 * k_row_bytes, ks + 16 * p * kRowBytes);
+      dma16(vp + vbase + (size_t)p * 16 * v_row_bytes, ks + 16 * p * kRowBytes + kTileBytes);
     }
   };
 
@@ -354,24 +350,25 @@ fwd_bf16_pp_kernel(KArgs a, int T, int n_rest) {
   bf16x8 qf[8];
   {
     const int tok = token_of(gidx * a.G + qrow, s, a.N);
-    const bf16x8* src = reinterpret_cast<const bf16x8*>(qp + ((size_t)((size_t)b * a.N + tok) * a.H + h) * 128);
+    const bf16x8* src = reinterpret_cast<const bf16x8*>(qp + row_off(a.sq, b, tok, h));
 #pragma unroll
     for (int st = 0; st < 8; ++st) qf[st] = src[2 * st + g32];
   }
 
   // staging: wave w, pass p fills tile rows 32p + 4w .. +3 of K and of V
   const int st_row = 4 * w + (lane >> 4);
-  const size_t kv_row_bytes = (size_t)a.Hkv * 256;
+  const size_t k_row_bytes = (size_t)a.sk.t * 2, v_row_bytes = (size_t)a.sv.t * 2;
   const uint32_t smem_base = lds_addr(smem);
-  const size_t st_goff = (size_t)st_row * kv_row_bytes + (size_t)(((lane & 15) ^ swz(st_row)) << 4);
+  const size_t st_chunk = (size_t)(((lane & 15) ^ swz(st_row)) << 4);
   auto issue_tile = [&](int n, int stage) {
     const int tok0 = token_of(gidx * a.G + (jt_first + n) * BN, s, a.N);
-    const size_t base = ((size_t)((size_t)b * a.N + tok0) * a.Hkv + c) * 256 + st_goff;
+    const size_t kbase = row_off(a.sk, b, tok0 + st_row, c) * 2 + st_chunk;
+    const size_t vbase = row_off(a.sv, b, tok0 + st_row, c) * 2 + st_chunk;
     const uint32_t ks = smem_base + stage * kStageBytes + 4 * w * kRowBytes;
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
-      dma16(kp + base + (size_t)p * 32 * kv_row_bytes, ks + 32 * p * kRowBytes);
-      dma16(vp + base + (size_t)p * 32 * kv_row_bytes, ks + 32 * p * kRowBytes + kTileBytes);
+      dma16(kp + kbase + (size_t)p * 32 * k_row_bytes, ks + 32 * p * kRowBytes);
+      dma16(vp + vbase + (size_t)p * 32 * v_row_bytes, ks + 32 * p * kRowBytes + kTileBytes);
     }
   };
 

@@ -6,6 +6,11 @@
 
 namespace s2 {
 
+// Element strides of one tensor: batch, token, head (the head-dim axis is contiguous).
+struct TStride {
+  long long b, t, h;
+};
+
 struct KArgs {
   const void* q; const void* k; const void* v;
   void* o; float* lse;                       // forward outputs / backward inputs
@@ -14,6 +19,8 @@ struct KArgs {
   float* delta;                              // (B,H,N) fp32
   float* lse2;                               // (B,H,N) fp32: lse * log2(e), written by the pre-pass
   float* dkv_partial;                        // fp32 [2 tensors][2 classes][B,N,Hkv,D] or null
+  TStride sq, sk, sv, sdq, sdk, sdv;         // q, k, v and their gradients may be strided views
+  TStride so;                                // o and dout: contiguous (B,N,H,D)
   int B, N, H, Hkv, D, G;
   int r;                                     // H / Hkv
   int shift;                                 // tokens, 0 <= shift < G
@@ -29,6 +36,11 @@ struct KArgs {
 __device__ __forceinline__ int token_of(int p, int s, int N) {
   int t = p + s;
   return t >= N ? t - N : t;
+}
+
+// Element offset of row (batch b, token t, head h) of a tensor.
+__device__ __forceinline__ size_t row_off(const TStride& s, int b, int t, int h) {
+  return (size_t)((long long)b * s.b + (long long)t * s.t + (long long)h * s.h);
 }
 
 __device__ __forceinline__ int shift_of_head(const KArgs& a, int h) {

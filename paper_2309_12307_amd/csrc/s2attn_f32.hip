@@ -18,7 +18,7 @@ constexpr int SLD = 65;  // leading dimension of score tiles in LDS
 // Loads rows [i0, i0+ROWS) of group g (in-group order) of one head into LDS,
 // zero-filling rows past the end of the group.
 template <int ROWS, int D>
-__device__ __forceinline__ void load_tile(float* dst, const float* src, int b, int head, int nheads,
+__device__ __forceinline__ void load_tile(float* dst, const float* src, const TStride& st, int b, int head,
                                           int g, int i0, int s, int N, int G) {
   constexpr int LD = D + 4;
   constexpr int C4 = D / 4;
@@ -28,7 +28,7 @@ __device__ __forceinline__ void load_tile(float* dst, const float* src, int b, i
     float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
     if (i < G) {
       int tok = token_of(g * G + i, s, N);
-      val = *reinterpret_cast<const float4*>(src + ((size_t)((size_t)b * N + tok) * nheads + head) * D + 4 * c4);
+      val = *reinterpret_cast<const float4*>(src + row_off(st, b, tok, head) + 4 * c4);
     }
     *reinterpret_cast<float4*>(dst + row * LD + 4 * c4) = val;
   }
@@ -79,7 +79,7 @@ __global__ void __launch_bounds__(kThreads) fwd_f32_kernel(KArgs a) {
   const float* k = static_cast<const float*>(a.k);
   const float* v = static_cast<const float*>(a.v);
 
-  load_tile<BM, D>(Qs, q, b, h, a.H, g, i0, s, a.N, a.G);
+  load_tile<BM, D>(Qs, q, a.sq, b, h, g, i0, s, a.N, a.G);
   if (tid < BM) { row_m[tid] = -1e30f; row_l[tid] = 0.f; }
   float o[4][DV][4];
 #pragma unroll
@@ -93,8 +93,8 @@ __global__ void __launch_bounds__(kThreads) fwd_f32_kernel(KArgs a) {
   for (int jt = jt_first; jt <= qt; ++jt) {
     const int j0 = jt * BN;
     __syncthreads();
-    load_tile<BN, D>(Ks, k, b, c, a.Hkv, g, j0, s, a.N, a.G);
-    load_tile<BN, D>(Vs, v, b, c, a.Hkv, g, j0, s, a.N, a.G);
+    load_tile<BN, D>(Ks, k, a.sk, b, c, g, j0, s, a.N, a.G);
+    load_tile<BN, D>(Vs, v, a.sv, b, c, g, j0, s, a.N, a.G);
     __syncthreads();
     float acc[4][4];
     tile_nt<4, D>(acc, Qs, Ks, ty, tx);
@@ -168,7 +168,7 @@ __global__ void __launch_bounds__(kThreads) fwd_f32_kernel(KArgs a) {
 #pragma unroll
     for (int e = 0; e < DV; ++e) {
       float4 val = make_float4(o[x][e][0] * inv, o[x][e][1] * inv, o[x][e][2] * inv, o[x][e][3] * inv);
-      *reinterpret_cast<float4*>(out + ((size_t)((size_t)b * a.N + tok) * a.H + h) * D + 4 * tx + 64 * e) = val;
+      *reinterpret_cast<float4*>(out + row_off(a.so, b, tok, h) + 4 * tx + 64 * e) = val;
     }
     if (tx == 0)
       a.lse[((size_t)b * a.H + h) * a.N + tok] = (row_m[row] + log2f(row_l[row])) * 0.6931471805599453f;
@@ -214,8 +214,8 @@ __global__ void __launch_bounds__(kThreads) bwd_dkdv_f32_kernel(KArgs a, int ncl
   const float* v = static_cast<const float*>(a.v);
   const float* dout = static_cast<const float*>(a.dout);
 
-  load_tile<BN, D>(Ks, k, b, c, a.Hkv, g, j0, s, a.N, a.G);
-  load_tile<BN, D>(Vs, v, b, c, a.Hkv, g, j0, s, a.N, a.G);
+  load_tile<BN, D>(Ks, k, a.sk, b, c, g, j0, s, a.N, a.G);
+  load_tile<BN, D>(Vs, v, a.sv, b, c, g, j0, s, a.N, a.G);
   float dk[4][DV][4], dv[4][DV][4];
 #pragma unroll
   for (int x = 0; x < 4; ++x)
@@ -230,8 +230,8 @@ __global__ void __launch_bounds__(kThreads) bwd_dkdv_f32_kernel(KArgs a, int ncl
       const int i0 = it * BQ;
       if (j0 + BN - 1 < split && i0 >= split) break;   // Variant 2: keys of the first block see no later rows
       __syncthreads();
-      load_tile<BQ, D>(Qs, q, b, h, a.H, g, i0, s, a.N, a.G);
-      load_tile<BQ, D>(dOs, dout, b, h, a.H, g, i0, s, a.N, a.G);
+      load_tile<BQ, D>(Qs, q, a.sq, b, h, g, i0, s, a.N, a.G);
+      load_tile<BQ, D>(dOs, dout, a.so, b, h, g, i0, s, a.N, a.G);
       if (tid < BQ) {
         int i = i0 + tid;
         float l = 0.f, dl = 0.f;
@@ -291,12 +291,15 @@ __global__ void __launch_bounds__(kThreads) bwd_dkdv_f32_kernel(KArgs a, int ncl
     int j = j0 + ty + 16 * x;
     if (j >= a.G) continue;
     int tok = token_of(g * a.G + j, s, a.N);
-    size_t base = ((size_t)((size_t)b * a.N + tok) * a.Hkv + c) * D + 4 * tx;
+    // fp32 partials of a mixed kv head are contiguous; final dk, dv may be strided views
+    const size_t cont = ((size_t)((size_t)b * a.N + tok) * a.Hkv + c) * D + 4 * tx;
+    const size_t base = a.dkv_partial ? cont : row_off(a.sdk, b, tok, c) + 4 * tx;
+    const size_t base_v = a.dkv_partial ? cont : row_off(a.sdv, b, tok, c) + 4 * tx;
 #pragma unroll
     for (int e = 0; e < DV; ++e) {
       *reinterpret_cast<float4*>(dk_out + base + 64 * e) =
           make_float4(dk[x][e][0] * a.scale, dk[x][e][1] * a.scale, dk[x][e][2] * a.scale, dk[x][e][3] * a.scale);
-      *reinterpret_cast<float4*>(dv_out + base + 64 * e) =
+      *reinterpret_cast<float4*>(dv_out + base_v + 64 * e) =
           make_float4(dv[x][e][0], dv[x][e][1], dv[x][e][2], dv[x][e][3]);
     }
   }
@@ -327,8 +330,8 @@ __global__ void __launch_bounds__(kThreads) bwd_dq_f32_kernel(KArgs a) {
   const float* v = static_cast<const float*>(a.v);
   const float* dout = static_cast<const float*>(a.dout);
 
-  load_tile<BQ, D>(Qs, q, b, h, a.H, g, i0, s, a.N, a.G);
-  load_tile<BQ, D>(dOs, dout, b, h, a.H, g, i0, s, a.N, a.G);
+  load_tile<BQ, D>(Qs, q, a.sq, b, h, g, i0, s, a.N, a.G);
+  load_tile<BQ, D>(dOs, dout, a.so, b, h, g, i0, s, a.N, a.G);
   if (tid < BQ) {
     int i = i0 + tid;
     float l = 0.f, dl = 0.f;
@@ -353,8 +356,8 @@ __global__ void __launch_bounds__(kThreads) bwd_dq_f32_kernel(KArgs a) {
   for (int jt = jt_first; jt <= jt_last; ++jt) {
     const int j0 = jt * BN;
     __syncthreads();
-    load_tile<BN, D>(Ks, k, b, c, a.Hkv, g, j0, s, a.N, a.G);
-    load_tile<BN, D>(Vs, v, b, c, a.Hkv, g, j0, s, a.N, a.G);
+    load_tile<BN, D>(Ks, k, a.sk, b, c, g, j0, s, a.N, a.G);
+    load_tile<BN, D>(Vs, v, a.sv, b, c, g, j0, s, a.N, a.G);
     __syncthreads();
     float sacc[2][4], pacc[2][4];
     tile_nt<2, D>(sacc, Qs, Ks, ty, tx);
@@ -394,7 +397,7 @@ __global__ void __launch_bounds__(kThreads) bwd_dq_f32_kernel(KArgs a) {
     int tok = token_of(g * a.G + i, s, a.N);
 #pragma unroll
     for (int e = 0; e < DV; ++e)
-      *reinterpret_cast<float4*>(out + ((size_t)((size_t)b * a.N + tok) * a.H + h) * D + 4 * tx + 64 * e) =
+      *reinterpret_cast<float4*>(out + row_off(a.sdq, b, tok, h) + 4 * tx + 64 * e) =
           make_float4(dq[x][e][0] * a.scale, dq[x][e][1] * a.scale, dq[x][e][2] * a.scale, dq[x][e][3] * a.scale);
   }
 }

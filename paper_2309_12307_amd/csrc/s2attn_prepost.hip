@@ -63,22 +63,30 @@ __global__ void __launch_bounds__(256) delta_kernel(const void* o, const void* d
 }
 
 template <bool BF16>
-__global__ void __launch_bounds__(256) combine_kernel(const float* partial, void* dk, void* dv, size_t elems) {
+__global__ void __launch_bounds__(256) combine_kernel(const float* partial, void* dk, void* dv, TStride sdk,
+                                                      TStride sdv, int N, int Hkv, int D, size_t elems) {
   const size_t i4 = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i4 >= elems) return;
+  // contiguous (b, t, c, d) index of the partials -> row of the (possibly strided) output
+  const int d = (int)(i4 % D);
+  const size_t row = i4 / D;
+  const int c = (int)(row % Hkv);
+  const size_t bt = row / Hkv;
+  const int t = (int)(bt % N), b = (int)(bt / N);
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const float4 x = *reinterpret_cast<const float4*>(partial + (size_t)(2 * t) * elems + i4);
-    const float4 y = *reinterpret_cast<const float4*>(partial + (size_t)(2 * t + 1) * elems + i4);
+  for (int which = 0; which < 2; ++which) {
+    const float4 x = *reinterpret_cast<const float4*>(partial + (size_t)(2 * which) * elems + i4);
+    const float4 y = *reinterpret_cast<const float4*>(partial + (size_t)(2 * which + 1) * elems + i4);
     const float r0 = x.x + y.x, r1 = x.y + y.y, r2 = x.z + y.z, r3 = x.w + y.w;
-    void* out = t == 0 ? dk : dv;
+    void* out = which == 0 ? dk : dv;
+    const size_t o = row_off(which == 0 ? sdk : sdv, b, t, c) + d;
     if (BF16) {
       uint2 pk;
       pk.x = f32_to_bf16_bits(r0) | (f32_to_bf16_bits(r1) << 16);
       pk.y = f32_to_bf16_bits(r2) | (f32_to_bf16_bits(r3) << 16);
-      *reinterpret_cast<uint2*>(static_cast<uint16_t*>(out) + i4) = pk;
+      *reinterpret_cast<uint2*>(static_cast<uint16_t*>(out) + o) = pk;
     } else {
-      *reinterpret_cast<float4*>(static_cast<float*>(out) + i4) = make_float4(r0, r1, r2, r3);
+      *reinterpret_cast<float4*>(static_cast<float*>(out) + o) = make_float4(r0, r1, r2, r3);
     }
   }
 }
@@ -99,9 +107,11 @@ int launch_combine_partials(const KArgs& a, int dtype, hipStream_t st) {
   const size_t elems = (size_t)a.B * a.N * a.Hkv * a.D;
   dim3 grid((unsigned)((elems / 4 + 255) / 256));
   if (dtype == S2ATTN_BF16)
-    hipLaunchKernelGGL(combine_kernel<true>, grid, dim3(256), 0, st, a.dkv_partial, a.dk, a.dv, elems);
+    hipLaunchKernelGGL(combine_kernel<true>, grid, dim3(256), 0, st, a.dkv_partial, a.dk, a.dv, a.sdk, a.sdv, a.N,
+                       a.Hkv, a.D, elems);
   else
-    hipLaunchKernelGGL(combine_kernel<false>, grid, dim3(256), 0, st, a.dkv_partial, a.dk, a.dv, elems);
+    hipLaunchKernelGGL(combine_kernel<false>, grid, dim3(256), 0, st, a.dkv_partial, a.dk, a.dv, a.sdk, a.sdv, a.N,
+                       a.Hkv, a.D, elems);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -55,3 +55,31 @@ def run_hip(inp: dict, G: int, dtype: str, backward=True, **ex):
 
 def max_abs(a, b):
     return float(np.max(np.abs(np.asarray(a, dtype=np.float64) - np.asarray(b, dtype=np.float64))))
+
+
+def run_hip_packed(inp: dict, G: int, dtype: str, **ex):
+    """Same as run_hip, but q, k, v are non-contiguous views into one packed
+    (B, N, H + 2*Hkv, D) tensor and dq, dk, dv views into one packed gradient tensor,
+    passed through the stride fields of the parameter block (no split copy)."""
+    bf = dtype == "bf16"
+    q = to_dev(inp["q"], inp.get("q_bits") if bf else None)
+    k = to_dev(inp["k"], inp.get("k_bits") if bf else None)
+    v = to_dev(inp["v"], inp.get("v_bits") if bf else None)
+    do = to_dev(inp["do"], inp.get("do_bits") if bf else None)
+    B, N, H, D = q.shape
+    Hkv = k.shape[2]
+    packed = torch.cat([q, k, v], dim=2).contiguous()
+    qv, kv, vv = packed[:, :, :H], packed[:, :, H:H + Hkv], packed[:, :, H + Hkv:]
+    assert not qv.is_contiguous()
+    o = torch.full_like(q, float("nan"))
+    lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    p = binding.make_params(qv, kv, vv, o, lse, G, strided=True, **ex)
+    binding.s2attn_fwd_ex(p)
+    dpacked = torch.full_like(packed, float("nan"))
+    dq, dk, dv = dpacked[:, :, :H], dpacked[:, :, H:H + Hkv], dpacked[:, :, H + Hkv:]
+    nbytes = binding.bwd_workspace_bytes(B, N, H, Hkv, D, G, binding.BF16 if bf else binding.F32)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    p = binding.make_params(qv, kv, vv, o, lse, G, dout=do, dq=dq, dk=dk, dv=dv, workspace=ws, strided=True, **ex)
+    binding.s2attn_bwd_ex(p)
+    torch.cuda.synchronize()
+    return dict(o=to_np(o), lse=to_np(lse), dq=to_np(dq), dk=to_np(dk), dv=to_np(dv))

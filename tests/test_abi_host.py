@@ -46,6 +46,9 @@ def params(**kw):
     p.workspace_bytes = kw.get("workspace_bytes", 1 << 40)
     for f in ("B", "N", "H", "Hkv", "D", "G", "dtype"):
         setattr(p, f, d[f])
+    for f in ("q", "k", "v", "dq", "dk", "dv"):
+        if f + "_strides" in kw:
+            setattr(p, f + "_strides", (ctypes.c_longlong * 3)(*kw[f + "_strides"]))
     p.shift = kw.get("shift", -1)
     p.shift_rule = kw.get("shift_rule", 0)
     p.wrap_variant = kw.get("wrap_variant", 0)
@@ -81,9 +84,20 @@ def test_validator_accepts_benchmark_shapes():
     (dict(shift_rule=7), -9),
     (dict(wrap_variant=1), -9),
     (dict(B=40000), -12),
+    (dict(q_strides=(1024 * 4 * 128 * 3, 3 * 4 * 128, 100)), -13),    # head stride not a multiple of 8
+    (dict(k_strides=(1024 * 4 * 128, -512, 128)), -13),               # negative
+    (dict(dv_strides=(1024 * 4 * 128, 512, 64)), -13),                # heads would overlap
 ])
 def test_validator_codes(kw, code):
     assert binding.check_args(params(**kw), True) == code
+
+
+def test_packed_qkv_strides_are_accepted():
+    # the three slices of a packed (B, N, 3, H, D) tensor
+    B, N, H, D = 1, 1024, 4, 128
+    st = (N * 3 * H * D, 3 * H * D, D)
+    p = params(q_strides=st, k_strides=st, v_strides=st, dq_strides=st, dk_strides=st, dv_strides=st)
+    assert binding.check_args(p, True) == 0
 
 
 def test_forward_check_ignores_backward_fields():

@@ -114,6 +114,18 @@ def test_variant2_split_wrap_group(shape):
     compare(out, ref)
 
 
+@pytest.mark.parametrize("shape", [(2, 1024, 4, 4, 128, 256), (1, 1536, 8, 2, 128, 512), (1, 768, 2, 1, 128, 256),
+                                   (1, 640, 2, 2, 128, 640)])
+def test_packed_qkv_views(shape):
+    """q, k, v (and dq, dk, dv) as strided views of one packed projection tensor."""
+    from gpu_util import run_hip_packed
+    B, N, H, Hkv, D, G = shape
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=190 + sum(shape), dtype="bf16")
+    out = run_hip_packed(inp, G, "bf16")
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G)
+    compare(out, ref)
+
+
 def test_outputs_are_deterministic():
     from gpu_util import run_hip
     inp = inputs.make_inputs(1, 1024, 4, 2, 128, seed=5, dtype="bf16")

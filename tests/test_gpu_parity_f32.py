@@ -97,6 +97,17 @@ def test_variant2_split_wrap_group(shape):
     compare(out, ref)
 
 
+@pytest.mark.parametrize("shape", [(2, 256, 4, 4, 64, 64), (1, 300, 6, 3, 64, 100), (1, 140, 2, 1, 128, 70)])
+def test_packed_qkv_views(shape):
+    """q, k, v (and dq, dk, dv) as strided views of one packed projection tensor."""
+    from gpu_util import run_hip_packed
+    B, N, H, Hkv, D, G = shape
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=90 + sum(shape), dtype="f32")
+    out = run_hip_packed(inp, G, "f32")
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G)
+    compare(out, ref)
+
+
 def test_outputs_are_deterministic():
     from gpu_util import run_hip
     cfg = inputs.CONFIGS["C1"]
