@@ -47,7 +47,9 @@ enum {
   S2ATTN_ERR_GROUP = -4,       /* N % G != 0, or G odd, or shift outside [0, G) */
   S2ATTN_ERR_HEADS = -5,       /* H odd (half of the heads shift), or H % Hkv != 0 */
   S2ATTN_ERR_HEADDIM = -6,     /* D not supported: fp32 needs D in {64,128}; bf16 needs D == 128 */
-  S2ATTN_ERR_TILE = -7,        /* bf16 path: G must be a multiple of 128 and shift of 64 */
+  S2ATTN_ERR_TILE = -7,        /* bf16 path with S2ATTN_WRAP_SPLIT: G must be a multiple of 128 and shift of 64
+                                  (S2ATTN_WRAP_JOINT takes any even G and any shift; multiples of 128 / 64
+                                  run the fast aligned path) */
   S2ATTN_ERR_WORKSPACE = -8,   /* backward workspace missing or too small */
   S2ATTN_ERR_DTYPE = -9,       /* unknown dtype / rule / variant value */
   S2ATTN_ERR_DEVICE = -10,     /* current device is not gfx950 */

@@ -69,7 +69,10 @@ int check_common(const s2attn_params* p, int backward) {
     if (p->D != 64 && p->D != 128) return S2ATTN_ERR_HEADDIM;
   } else {
     if (p->D != 128) return S2ATTN_ERR_HEADDIM;
-    if (p->G % 128 != 0 || shift % 64 != 0) return S2ATTN_ERR_TILE;
+    // Variant 2 moves the first visible key of a tile row block; the bf16 kernels only
+    // do that at tile boundaries
+    if (p->wrap_variant == S2ATTN_WRAP_SPLIT && shift > 0 && (p->G % 128 != 0 || shift % 64 != 0))
+      return S2ATTN_ERR_TILE;
   }
   // grid z carries batch * heads (* 2 classes); element offsets are 64-bit
   if ((long long)p->B * p->H * 2 > 65535 || (long long)p->N / p->G > 65535) return S2ATTN_ERR_TOO_LARGE;
@@ -148,6 +151,7 @@ s2::KArgs make_kargs(const s2attn_params* p) {
   a.shifted_from = shifted_from(p->shift_rule, p->H, a.shift);
   a.split = (p->wrap_variant == S2ATTN_WRAP_SPLIT && a.shift > 0) ? p->G - a.shift : p->G;
   a.mixed = kv_heads_mixed(p->H, p->Hkv, a.shifted_from) ? 1 : 0;
+  a.ragged = (p->dtype == S2ATTN_BF16 && (p->G % 128 != 0 || a.shift % 64 != 0)) ? 1 : 0;
   a.scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->D);
   a.scale_log2 = a.scale * 1.4426950408889634f;
   return a;
@@ -268,7 +272,7 @@ const char* s2attn_strerror(int code) {
     case S2ATTN_ERR_GROUP: return "need N % G == 0, G even and 0 <= shift < G";
     case S2ATTN_ERR_HEADS: return "need H even and H % Hkv == 0";
     case S2ATTN_ERR_HEADDIM: return "unsupported head dimension (fp32: 64 or 128; bf16: 128)";
-    case S2ATTN_ERR_TILE: return "bf16 path needs G to be a multiple of 128 and shift a multiple of 64";
+    case S2ATTN_ERR_TILE: return "bf16 path with the split wrap-around group needs G to be a multiple of 128 and shift a multiple of 64";
     case S2ATTN_ERR_WORKSPACE: return "backward workspace missing or smaller than s2attn_bwd_workspace_bytes";
     case S2ATTN_ERR_DTYPE: return "unknown dtype, shift rule or wrap variant";
     case S2ATTN_ERR_DEVICE: return "current device is not gfx950 (MI355X)";

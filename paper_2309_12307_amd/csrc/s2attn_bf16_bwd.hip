@@ -84,10 +84,11 @@ __device__ __forceinline__ void mma_acc(const bf16x8 (&buf)[8], const bf16x4 (&p
   }
 }
 // P and dS for accumulator registers 4*QTR .. 4*QTR+3 of block MB (4 consecutive queries
-// per lane half), packed to bf16.  MASK: causal mask against this lane's key.
+// per lane half), packed to bf16.  MASK: causal mask against this lane's key, and query
+// rows at or past q_lim (padding of a partial tile) contribute nothing.
 template <int MB, int QTR, bool MASK>
 __device__ __forceinline__ void sm_quarter(const DkdvBlock& blk, const DkdvTile& t, bf16x4& pq, bf16x4& dsq,
-                                           int q_first = 0, int key = 0) {
+                                           int q_first = 0, int key = 0, int q_lim = INT32_MAX) {
   const float4 l4 = *reinterpret_cast<const float4*>(t.lse2_s + 32 * MB + 8 * QTR + 4 * t.g32);
   const float4 d4 = *reinterpret_cast<const float4*>(t.delta_s + 32 * MB + 8 * QTR + 4 * t.g32);
   const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
@@ -98,7 +99,7 @@ __device__ __forceinline__ void sm_quarter(const DkdvBlock& blk, const DkdvTile&
     float pv = __builtin_amdgcn_exp2f(fmaf(blk.s[v], t.c2, -ls[e]));
     if (MASK) {
       const int qrow = q_first + 8 * QTR + 4 * t.g32 + e;
-      if (key > qrow) pv = 0.f;
+      if (key > qrow || qrow >= q_lim) pv = 0.f;
     }
     p[e] = pv;
     ds[e] = pv * (blk.dp[v] - dl[e]);
@@ -156,7 +157,8 @@ __device__ __forceinline__ void dkdv_interior_tile(const DkdvTile& t, const bf16
 // One 32-query block without pipelining (diagonal tiles).
 template <bool MASK>
 __device__ __forceinline__ void dkdv_block(const DkdvTile& t, int mb, int q_first, int key, const bf16x8 (&kf)[8],
-                                           const bf16x8 (&vf)[8], f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4]) {
+                                           const bf16x8 (&vf)[8], f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4],
+                                           int q_lim = INT32_MAX) {
   DkdvTile tt = t;
   tt.Qs += mb * 32 * kRowBytes;     // rows of a tile are swizzled by (row & 15) only, so a
   tt.dOs += mb * 32 * kRowBytes;    // block is addressed by moving the base by 32 rows
@@ -169,14 +171,18 @@ __device__ __forceinline__ void dkdv_block(const DkdvTile& t, int mb, int q_firs
   load_sc<0, 0>(fa, tt); load_sc<0, 1>(fb, tt);
   mma_sc<0>(fa, blk, kf, vf); mma_sc<1>(fb, blk, kf, vf);
   load_acc<0, 0>(fa, tt); load_acc<0, 1>(fb, tt);
-  sm_quarter<0, 0, MASK>(blk, tt, pq[0], dsq[0], q_first, key);
-  sm_quarter<0, 1, MASK>(blk, tt, pq[1], dsq[1], q_first, key);
-  sm_quarter<0, 2, MASK>(blk, tt, pq[2], dsq[2], q_first, key);
-  sm_quarter<0, 3, MASK>(blk, tt, pq[3], dsq[3], q_first, key);
+  sm_quarter<0, 0, MASK>(blk, tt, pq[0], dsq[0], q_first, key, q_lim);
+  sm_quarter<0, 1, MASK>(blk, tt, pq[1], dsq[1], q_first, key, q_lim);
+  sm_quarter<0, 2, MASK>(blk, tt, pq[2], dsq[2], q_first, key, q_lim);
+  sm_quarter<0, 3, MASK>(blk, tt, pq[3], dsq[3], q_first, key, q_lim);
   mma_acc<0>(fa, pq, dsq, dk_acc, dv_acc);
   mma_acc<1>(fb, pq, dsq, dk_acc, dv_acc);
 }
 
+// RAGGED: G is not a multiple of 128 or the shift not of 64 -- tiles may be partial and
+// the wrap point may fall inside one, so every staged row finds its own token and the
+// padding rows of the last tile are masked.  The aligned instantiation carries none of it.
+template <bool RAGGED>
 __global__ void __launch_bounds__(256, 1)
 bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
   __shared__ __attribute__((aligned(1024))) char smem[4 * kQTileBytes];            // [stage][Q,dO]
@@ -221,15 +227,15 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
   // K^T and V^T fragments of this wave's 32 keys
   bf16x8 kf[8], vf[8];
   {
-    const int tok = token_of(gidx * a.G + key, s, a.N);
+    const int tok = row_token(a, gidx, key, s);
     const bf16x8* ksrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.k) + row_off(a.sk, b, tok, c));
     const bf16x8* vsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.v) + row_off(a.sv, b, tok, c));
 #pragma unroll
     for (int st = 0; st < 8; ++st) { kf[st] = ksrc[2 * st + g32]; vf[st] = vsrc[2 * st + g32]; }
   }
 
-  // staging: wave w, pass p fills tile rows 16p + 4w .. +3 (1 KB); every 64 rows of a
-  // tile are one contiguous token run (shift and G are multiples of 64).
+  // staging: wave w, pass p fills tile rows 16p + 4w .. +3 (1 KB); in the aligned case
+  // (shift and G multiples of 64) every 64 rows of a tile are one contiguous token run.
   const uint32_t smem_base = lds_addr(smem);
   const uint32_t rows_base = lds_addr(rows_s);
   const size_t q_row_bytes = (size_t)a.sq.t * 2, do_row_bytes = (size_t)a.so.t * 2;
@@ -241,18 +247,33 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
     const uint32_t qs = smem_base + stage * 2 * kQTileBytes + 4 * w * kRowBytes;
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
-      const int tok0 = token_of(gidx * a.G + q0 + 64 * hf, s, a.N);
-      const size_t qbase = row_off(a.sq, b, tok0 + st_row, h) * 2 + st_chunk;
-      const size_t dobase = row_off(a.so, b, tok0 + st_row, h) * 2 + st_chunk;
+      if constexpr (!RAGGED) {
+        const int tok0 = token_of(gidx * a.G + q0 + 64 * hf, s, a.N);
+        const size_t qbase = row_off(a.sq, b, tok0 + st_row, h) * 2 + st_chunk;
+        const size_t dobase = row_off(a.so, b, tok0 + st_row, h) * 2 + st_chunk;
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        dma16(qp + qbase + (size_t)p * 16 * q_row_bytes, qs + (64 * hf + 16 * p) * kRowBytes);
-        dma16(dop + dobase + (size_t)p * 16 * do_row_bytes, qs + (64 * hf + 16 * p) * kRowBytes + kQTileBytes);
-      }
-      if (w == hf) {   // wave 0 / 1: lse and delta of rows 64*hf .. +63
-        const size_t ro = ((size_t)b * a.H + h) * a.N + tok0 + lane;
-        dma4(a.lse2 + ro, rows_base + ((stage * 2 + 0) * kQTileRows + 64 * hf) * 4);
-        dma4(a.delta + ro, rows_base + ((stage * 2 + 1) * kQTileRows + 64 * hf) * 4);
+        for (int p = 0; p < 4; ++p) {
+          dma16(qp + qbase + (size_t)p * 16 * q_row_bytes, qs + (64 * hf + 16 * p) * kRowBytes);
+          dma16(dop + dobase + (size_t)p * 16 * do_row_bytes, qs + (64 * hf + 16 * p) * kRowBytes + kQTileBytes);
+        }
+        if (w == hf) {   // wave 0 / 1: lse and delta of rows 64*hf .. +63
+          const size_t ro = ((size_t)b * a.H + h) * a.N + tok0 + lane;
+          dma4(a.lse2 + ro, rows_base + ((stage * 2 + 0) * kQTileRows + 64 * hf) * 4);
+          dma4(a.delta + ro, rows_base + ((stage * 2 + 1) * kQTileRows + 64 * hf) * 4);
+        }
+      } else {   // every row finds its own token; padding rows repeat the last row of the group
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int tok = row_token(a, gidx, q0 + 64 * hf + 16 * p + st_row, s);
+          dma16(qp + row_off(a.sq, b, tok, h) * 2 + st_chunk, qs + (64 * hf + 16 * p) * kRowBytes);
+          dma16(dop + row_off(a.so, b, tok, h) * 2 + st_chunk,
+                qs + (64 * hf + 16 * p) * kRowBytes + kQTileBytes);
+        }
+        if (w == hf) {
+          const size_t ro = ((size_t)b * a.H + h) * a.N + row_token(a, gidx, q0 + 64 * hf + lane, s);
+          dma4(a.lse2 + ro, rows_base + ((stage * 2 + 0) * kQTileRows + 64 * hf) * 4);
+          dma4(a.delta + ro, rows_base + ((stage * 2 + 1) * kQTileRows + 64 * hf) * 4);
+        }
       }
     }
   };
@@ -269,6 +290,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
     wait_vmcnt0();
     __syncthreads();
     if (n + 1 < n_iter) issue_tile(n + 1, stage ^ 1);
+    if constexpr (RAGGED) __builtin_amdgcn_sched_barrier(0);   // keeps the per-row addresses out of the tile body
     const int q0 = (it_begin + uni(n % nq)) * kQTileRows;
     DkdvTile t;
     t.Qs = smem + stage * 2 * kQTileBytes;
@@ -278,8 +300,14 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
     t.c2 = c2; t.g32 = g32; t.lo = lo;
     // Variant 2: keys of the first block see no query of the second block
     if (kw0 + 31 < split && q0 >= split) continue;
-    if (q0 > j0) {
+    if (q0 > j0 && !(RAGGED && q0 + kQTileRows > a.G)) {
       dkdv_interior_tile(t, kf, vf, dk_acc, dv_acc);
+    } else if constexpr (RAGGED) {
+      // diagonal tile and/or partial last tile: the padding rows of a partial tile must not
+      // reach dK/dV, so every block takes the masked path (query rows >= G give P = 0);
+      // on the diagonal tile the blocks before this wave's keys are skipped
+      for (int mb = (q0 > j0 ? 0 : w); mb < 4; ++mb)
+        dkdv_block<true>(t, mb, q0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, a.G);
     } else {
       // diagonal tile: block mb < w is entirely before this wave's keys, block w is masked
       dkdv_block<true>(t, w, q0 + 32 * w, key, kf, vf, dk_acc, dv_acc);
@@ -294,6 +322,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
     const size_t kv_elems = (size_t)a.B * a.N * a.Hkv * 128;
     float* dk_out = a.dkv_partial + (size_t)cls * kv_elems;
     float* dv_out = a.dkv_partial + (size_t)(2 + cls) * kv_elems;
+    if (key >= a.G) return;   // padding key of a partial tile
     const int tok = token_of(gidx * a.G + key, s, a.N);
     const size_t base = ((size_t)((size_t)b * a.N + tok) * a.Hkv + c) * 128;   // partials are contiguous
 #pragma unroll
@@ -319,6 +348,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
+    if (kw0 + row >= a.G) continue;   // padding key of a partial tile
     const int tok = token_of(gidx * a.G + kw0 + row, s, a.N);
     *reinterpret_cast<uint4*>(dkp + row_off(a.sdk, b, tok, c) + ch * 8) =
         *reinterpret_cast<const uint4*>(rk + tile_off(row, ch));
@@ -416,6 +446,7 @@ __device__ __forceinline__ void dq_tile(f32x16 (&dq_acc)[4], const bf16x8 (&qf)[
 #undef S2_DQ_STEP
 }
 
+template <bool RAGGED>
 __global__ void __launch_bounds__(256, 2)
 bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
   constexpr int BM = 128;
@@ -452,7 +483,7 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
   bf16x8 qf[8], dof[8];
   float lse2, delta;
   {
-    const int tok = token_of(gidx * a.G + qrow, s, a.N);
+    const int tok = row_token(a, gidx, qrow, s);
     const bf16x8* qsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.q) + row_off(a.sq, b, tok, h));
     const bf16x8* dsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.dout) + row_off(a.so, b, tok, h));
 #pragma unroll
@@ -467,14 +498,23 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
   const int st_row = 4 * w + (lane >> 4);
   const size_t st_chunk = (size_t)(((lane & 15) ^ swz(st_row)) << 4);
   auto issue_tile = [&](int jt, int stage) {
-    const int tok0 = token_of(gidx * a.G + jt * BN, s, a.N);
-    const size_t kbase = row_off(a.sk, b, tok0 + st_row, c) * 2 + st_chunk;
-    const size_t vbase = row_off(a.sv, b, tok0 + st_row, c) * 2 + st_chunk;
     const uint32_t ks = smem_base + stage * 2 * kTileBytes + 4 * w * kRowBytes;
+    if constexpr (!RAGGED) {
+      const int tok0 = token_of(gidx * a.G + jt * BN, s, a.N);   // an aligned tile never straddles the wrap
+      const size_t kbase = row_off(a.sk, b, tok0 + st_row, c) * 2 + st_chunk;
+      const size_t vbase = row_off(a.sv, b, tok0 + st_row, c) * 2 + st_chunk;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      dma16(kp + kbase + (size_t)p * 16 * k_row_bytes, ks + 16 * p * kRowBytes);
-      dma16(vp + vbase + (size_t)p * 16 * v_row_bytes, ks + 16 * p * kRowBytes + kTileBytes);
+      for (int p = 0; p < 4; ++p) {
+        dma16(kp + kbase + (size_t)p * 16 * k_row_bytes, ks + 16 * p * kRowBytes);
+        dma16(vp + vbase + (size_t)p * 16 * v_row_bytes, ks + 16 * p * kRowBytes + kTileBytes);
+      }
+    } else {   // every row finds its own token; padding rows repeat the last row of the group
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int tok = row_token(a, gidx, jt * BN + 16 * p + st_row, s);
+        dma16(kp + row_off(a.sk, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes);
+        dma16(vp + row_off(a.sv, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes + kTileBytes);
+      }
     }
   };
 
@@ -513,6 +553,7 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
+    if (qw0 + row >= a.G) continue;   // padding row of a partial tile
     const int tok = token_of(gidx * a.G + qw0 + row, s, a.N);
     *reinterpret_cast<uint4*>(dqp + row_off(a.sdq, b, tok, h) + ch * 8) =
         *reinterpret_cast<const uint4*>(region + tile_off(row, ch));
@@ -524,19 +565,25 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
 int launch_bwd_dkdv_bf16(const KArgs& a, hipStream_t st) {
   const int NG = a.N / a.G;
   const int ncls = a.mixed ? 2 : 1;
-  const int T = a.G / 128;
+  const int T = (a.G + 127) / 128;
   const int n_rest = a.B * a.Hkv * ncls * NG;
   const int blocks = 8 * T * ((n_rest + 7) / 8);
-  hipLaunchKernelGGL(bwd_dkdv_bf16_kernel, dim3(blocks), dim3(256), 0, st, a, ncls, T, n_rest);
+  if (a.ragged)
+    hipLaunchKernelGGL(bwd_dkdv_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, ncls, T, n_rest);
+  else
+    hipLaunchKernelGGL(bwd_dkdv_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, ncls, T, n_rest);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_bwd_dq_bf16(const KArgs& a, hipStream_t st) {
   const int NG = a.N / a.G;
-  const int T = a.G / 128;
+  const int T = (a.G + 127) / 128;
   const int n_rest = a.B * a.Hkv * NG;
   const int blocks = 8 * T * a.r * ((n_rest + 7) / 8);
-  hipLaunchKernelGGL(bwd_dq_bf16_kernel, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
+  if (a.ragged)
+    hipLaunchKernelGGL(bwd_dq_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
+  else
+    hipLaunchKernelGGL(bwd_dq_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -153,15 +153,20 @@ __device__ __forceinline__ void fwd_epilogue(const KArgs& a, FwdState& st, char*
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
     const uint4 val = *reinterpret_cast<const uint4*>(Os + tile_off(row, ch));
-    const int tok = token_of(gidx * a.G + qw0 + row, s, a.N);
-    *reinterpret_cast<uint4*>(op + row_off(a.so, b, tok, h) + ch * 8) = val;
+    if (qw0 + row < a.G) {   // rows past the group end are padding of a partial tile
+      const int tok = token_of(gidx * a.G + qw0 + row, s, a.N);
+      *reinterpret_cast<uint4*>(op + row_off(a.so, b, tok, h) + ch * 8) = val;
+    }
   }
-  if (g32 == 0) {
+  if (g32 == 0 && qw0 + l32 < a.G) {
     const int tok = token_of(gidx * a.G + qw0 + l32, s, a.N);
     a.lse[((size_t)b * a.H + h) * a.N + tok] = (st.m_run * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
   }
 }
 
+// RAGGED: G is not a multiple of 128 or the shift not of 64 -- tiles may be partial and
+// the wrap point may fall inside one, so every staged row finds its own token.
+template <bool RAGGED>
 __global__ void __launch_bounds__(256, 2)
 fwd_bf16_kernel(KArgs a, int T, int n_rest) {
   constexpr int BM = 128;
@@ -204,7 +209,7 @@ fwd_bf16_kernel(KArgs a, int T, int n_rest) {
   // ---- Q^T fragments of this wave, straight from global memory
   bf16x8 qf[8];
   {
-    const int tok = token_of(gidx * a.G + qrow, s, a.N);
+    const int tok = row_token(a, gidx, qrow, s);
     const bf16x8* src = reinterpret_cast<const bf16x8*>(qp + row_off(a.sq, b, tok, h));
 #pragma unroll
     for (int st = 0; st < 8; ++st) qf[st] = src[2 * st + g32];
@@ -218,14 +223,23 @@ fwd_bf16_kernel(KArgs a, int T, int n_rest) {
   const uint32_t smem_base = lds_addr(smem);
   const size_t st_chunk = (size_t)(((lane & 15) ^ swz(st_row)) << 4);
   auto issue_tile = [&](int jt, int stage) {
-    const int tok0 = token_of(gidx * a.G + jt * BN, s, a.N);   // a tile never straddles the wrap
-    const size_t kbase = row_off(a.sk, b, tok0 + st_row, c) * 2 + st_chunk;
-    const size_t vbase = row_off(a.sv, b, tok0 + st_row, c) * 2 + st_chunk;
     const uint32_t ks = smem_base + stage * 2 * kTileBytes + 4 * w * kRowBytes;
+    if constexpr (!RAGGED) {
+      const int tok0 = token_of(gidx * a.G + jt * BN, s, a.N);   // an aligned tile never straddles the wrap
+      const size_t kbase = row_off(a.sk, b, tok0 + st_row, c) * 2 + st_chunk;
+      const size_t vbase = row_off(a.sv, b, tok0 + st_row, c) * 2 + st_chunk;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      dma16(kp + kbase + (size_t)p * 16 * k_row_bytes, ks + 16 * p * kRowBytes);
-      dma16(vp + vbase + (size_t)p * 16 * v_row_bytes, ks + 16 * p * kRowBytes + kTileBytes);
+      for (int p = 0; p < 4; ++p) {
+        dma16(kp + kbase + (size_t)p * 16 * k_row_bytes, ks + 16 * p * kRowBytes);
+        dma16(vp + vbase + (size_t)p * 16 * v_row_bytes, ks + 16 * p * kRowBytes + kTileBytes);
+      }
+    } else {   // every row finds its own token; padding rows repeat the last row of the group
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int tok = row_token(a, gidx, jt * BN + 16 * p + st_row, s);
+        dma16(kp + row_off(a.sk, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes);
+        dma16(vp + row_off(a.sv, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes + kTileBytes);
+      }
     }
   };
 
@@ -458,16 +472,19 @@ fwd_bf16_pp_kernel(KArgs a, int T, int n_rest) {
 
 int launch_fwd_bf16(const KArgs& a, hipStream_t st) {
   const int n_groups = a.B * a.Hkv * (a.N / a.G);
-  if (a.G % 256 == 0) {
+  if (a.G % 256 == 0 && !a.ragged) {
     const int T = a.G / 256;
     const int blocks = 8 * T * a.r * ((n_groups + 7) / 8);
     hipLaunchKernelGGL(fwd_bf16_pp_kernel, dim3(blocks), dim3(512), 0, st, a, T, n_groups);
     return hipGetLastError() == hipSuccess ? 0 : -1;
   }
-  const int T = a.G / 128;
+  const int T = (a.G + 127) / 128;
   const int n_rest = a.B * a.Hkv * (a.N / a.G);
   const int blocks = 8 * T * a.r * ((n_rest + 7) / 8);
-  hipLaunchKernelGGL(fwd_bf16_kernel, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
+  if (a.ragged)
+    hipLaunchKernelGGL(fwd_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
+  else
+    hipLaunchKernelGGL(fwd_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

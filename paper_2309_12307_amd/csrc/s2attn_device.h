@@ -27,6 +27,8 @@ struct KArgs {
   int shifted_from;                          // heads >= shifted_from use the shifted partition
   int split;                                 // Variant 2: rows [0,split) | [split,G) of the wrap group; G = off
   int mixed;                                 // some kv head serves both head classes
+  int ragged;                                // bf16 path: G % 128 != 0 or shift % 64 != 0 (partial tiles,
+                                             // wrap point inside a tile)
   float scale;                               // softmax scale
   float scale_log2;                          // scale * log2(e)
 };
@@ -41,6 +43,12 @@ __device__ __forceinline__ int token_of(int p, int s, int N) {
 // Element offset of row (batch b, token t, head h) of a tensor.
 __device__ __forceinline__ size_t row_off(const TStride& s, int b, int t, int h) {
   return (size_t)((long long)b * s.b + (long long)t * s.t + (long long)h * s.h);
+}
+
+// Token of in-group row i of group g, with rows past the end of the group (padding of a
+// partial tile) clamped to the last row so that every load stays inside the tensor.
+__device__ __forceinline__ int row_token(const KArgs& a, int g, int i, int s) {
+  return token_of(g * a.G + min(i, a.G - 1), s, a.N);
 }
 
 __device__ __forceinline__ int shift_of_head(const KArgs& a, int h) {

@@ -77,7 +77,8 @@ def test_validator_accepts_benchmark_shapes():
     (dict(H=4, Hkv=3), -5),
     (dict(D=96), -6),
     (dict(D=64), -6),                         # bf16 supports D = 128 only
-    (dict(G=64, N=1024), -7),
+    (dict(G=200, N=1000, wrap_variant=2), -7),  # Variant 2 needs tile-aligned G and shift in bf16
+    (dict(shift=100, wrap_variant=2), -7),
     (dict(workspace_bytes=16), -8),
     (dict(workspace=0), -8),
     (dict(dtype=5), -9),
@@ -90,6 +91,17 @@ def test_validator_accepts_benchmark_shapes():
 ])
 def test_validator_codes(kw, code):
     assert binding.check_args(params(**kw), True) == code
+
+
+@pytest.mark.parametrize("kw", [
+    dict(G=64, N=1024),                 # group smaller than a tile
+    dict(G=200, N=1000),                # partial last tile, shift 100 inside a tile
+    dict(G=25000, N=100000),            # the paper's 100k-token setting (Section 4.2), G = N / 4
+    dict(shift=2),
+    dict(wrap_variant=2),               # aligned Variant 2
+])
+def test_validator_accepts_unaligned_groups_in_bf16(kw):
+    assert binding.check_args(params(**kw), True) == 0
 
 
 def test_packed_qkv_strides_are_accepted():

@@ -126,6 +126,58 @@ def test_packed_qkv_views(shape):
     compare(out, ref)
 
 
+# Group sizes and shifts that are not multiples of the kernels' tile sizes (128 rows,
+# 64-token runs): partial last tiles and a wrap point inside a tile.
+RAGGED_SHAPES = [
+    (1, 400, 2, 2, 128, 200),      # two tiles per group, the second partial; shift 100
+    (1, 192, 2, 1, 128, 64),       # group smaller than a tile, MQA (both classes share the kv head)
+    (2, 780, 4, 4, 128, 390),      # batch 2, four tiles with a 6-row tail
+    (1, 1000, 4, 2, 128, 500),     # GQA
+    (1, 1000, 2, 2, 128, 1000),    # one group; last wave of the last tile is all padding
+    (1, 1290, 6, 3, 128, 258),     # two-row tail; odd Hkv: middle kv head is mixed
+    (1, 10000, 2, 2, 128, 2500),   # N = 100000, G = 25000 (Section 4.2) scaled down by 10
+]
+
+
+@pytest.mark.parametrize("shape", RAGGED_SHAPES)
+def test_unaligned_group_sizes(shape):
+    from gpu_util import run_hip
+    B, N, H, Hkv, D, G = shape
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=300 + sum(shape), dtype="bf16")
+    out = run_hip(inp, G, "bf16")
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, dtype=np.float32)
+    compare(out, ref)
+
+
+@pytest.mark.parametrize("G,shift", [(256, 2), (256, 100), (512, 447), (200, 1), (200, 199)])
+def test_unaligned_shift(G, shift):
+    from gpu_util import run_hip
+    B, N, H, Hkv, D = 1, 4 * G, 4, 2, 128
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=320 + G + shift, dtype="bf16")
+    out = run_hip(inp, G, "bf16", shift=shift)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, shift=shift)
+    compare(out, ref)
+
+
+@pytest.mark.parametrize("rule,name", [(1, "none"), (2, "all")])
+def test_unaligned_group_shift_rules(rule, name):
+    from gpu_util import run_hip
+    B, N, H, Hkv, D, G = 1, 900, 4, 2, 128, 300
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=330 + rule, dtype="bf16")
+    out = run_hip(inp, G, "bf16", shift_rule=rule)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, shift_heads=name)
+    compare(out, ref)
+
+
+def test_unaligned_group_packed_qkv_views():
+    from gpu_util import run_hip_packed
+    B, N, H, Hkv, D, G = 1, 1000, 4, 2, 128, 500
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=340, dtype="bf16")
+    out = run_hip_packed(inp, G, "bf16")
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G)
+    compare(out, ref)
+
+
 def test_outputs_are_deterministic():
     from gpu_util import run_hip
     inp = inputs.make_inputs(1, 1024, 4, 2, 128, seed=5, dtype="bf16")

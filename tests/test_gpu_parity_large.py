@@ -26,9 +26,9 @@ def check(name, got, ref, heads_summed=1):
     return float(err.max())
 
 
-def run_and_check(cfg_name, slices):
+def run_and_check(cfg_name, slices, cfg=None):
     from gpu_util import run_hip
-    cfg = inputs.CONFIGS[cfg_name]
+    cfg = cfg or inputs.CONFIGS[cfg_name]
     inp = inputs.make_config_inputs(cfg)
     out = run_hip(inp, cfg.G, "bf16")
     N, G, H, Hkv = cfg.N, cfg.G, cfg.H, cfg.Hkv
@@ -74,3 +74,11 @@ def test_config_c4_gqa_sampled_slices():
 def test_config_c5_100k_sampled_slices():
     # N = 102400, G = 25600: one unshifted group and the wrap-around group
     run_and_check("C5", [(3, 1), (31, 3)])
+
+
+def test_100k_tokens_unaligned_group():
+    # the paper's longest 7B context (Section 4.2) at its exact length: N = 100000 with
+    # G = N / 4 = 25000 and shift 12500, neither a multiple of the kernels' tile sizes;
+    # 4 heads keep the run short.  A first group, and the wrap-around group of a shifted head.
+    cfg = inputs.S2Config("N100000", 6, "bf16", 1, 100000, 4, 4, 128, 25000)
+    run_and_check("N100000", [(1, 0), (3, 3)], cfg)
