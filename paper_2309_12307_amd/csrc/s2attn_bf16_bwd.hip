@@ -241,9 +241,9 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
   const size_t q_row_bytes = (size_t)a.sq.t * 2, do_row_bytes = (size_t)a.so.t * 2;
   const int st_row = 4 * w + (lane >> 4);
   const size_t st_chunk = (size_t)(((lane & 15) ^ swz(st_row)) << 4);
-  auto issue_tile = [&](int n, int stage) {
-    const int h = h_lo + uni(n / nq);
-    const int q0 = (it_begin + uni(n % nq)) * kQTileRows;
+  auto issue_tile = [&](int hh, int it, int stage) {
+    const int h = h_lo + hh;
+    const int q0 = (it_begin + it) * kQTileRows;
     const uint32_t qs = smem_base + stage * 2 * kQTileBytes + 4 * w * kRowBytes;
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
@@ -284,34 +284,58 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
 #pragma unroll
   for (int db = 0; db < 4; ++db) { dk_acc[db] = zero16(); dv_acc[db] = zero16(); }
 
-  if (n_iter > 0) issue_tile(0, 0);
-  for (int n = 0; n < n_iter; ++n) {
+  // Tile n = hh * nq + it is query tile it_begin + it of head h_lo + hh.  Waits for its
+  // staged data, starts the staging of tile n + 1 into the other stage and describes the tile.
+  auto begin_tile = [&](int n, int hh, int it) {
     const int stage = n & 1;
     wait_vmcnt0();
     __syncthreads();
-    if (n + 1 < n_iter) issue_tile(n + 1, stage ^ 1);
+    if (n + 1 < n_iter) {
+      const bool wrap = it + 1 == nq;
+      issue_tile(wrap ? hh + 1 : hh, wrap ? 0 : it + 1, stage ^ 1);
+    }
     if constexpr (RAGGED) __builtin_amdgcn_sched_barrier(0);   // keeps the per-row addresses out of the tile body
-    const int q0 = (it_begin + uni(n % nq)) * kQTileRows;
     DkdvTile t;
     t.Qs = smem + stage * 2 * kQTileBytes;
     t.dOs = t.Qs + kQTileBytes;
     t.lse2_s = rows_s[stage][0];
     t.delta_s = rows_s[stage][1];
     t.c2 = c2; t.g32 = g32; t.lo = lo;
-    // Variant 2: keys of the first block see no query of the second block
-    if (kw0 + 31 < split && q0 >= split) continue;
-    if (q0 > j0 && !(RAGGED && q0 + kQTileRows > a.G)) {
+    return t;
+  };
+
+  // Per head: the diagonal tile first, then the interior tiles in a loop of their own (the
+  // hot loop holds nothing but the pipelined interior tile), then, for a group size that is
+  // not a multiple of the tile, the partial last tile.
+  const bool has_tail = RAGGED && (a.G % kQTileRows != 0);
+  const int n_full = has_tail ? nq - 1 : nq;           // tiles [0, n_full) are complete
+  if (n_iter > 0) issue_tile(0, 0, 0);
+  int n = 0;
+  for (int hh = 0; hh < nheads; ++hh) {
+    {
+      const DkdvTile t = begin_tile(n, hh, 0);
+      if constexpr (RAGGED) {
+        // query rows >= G (padding of a partial tile) give P = 0; blocks before this wave's
+        // keys are skipped
+        for (int mb = w; mb < 4; ++mb) dkdv_block<true>(t, mb, j0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, a.G);
+      } else {
+        // block mb < w is entirely before this wave's keys, block w is masked
+        dkdv_block<true>(t, w, j0 + 32 * w, key, kf, vf, dk_acc, dv_acc);
+        for (int mb = w + 1; mb < 4; ++mb) dkdv_block<false>(t, mb, 0, key, kf, vf, dk_acc, dv_acc);
+      }
+      ++n;
+    }
+    for (int it = 1; it < n_full; ++it, ++n) {
+      const DkdvTile t = begin_tile(n, hh, it);
+      // Variant 2: keys of the first block see no query of the second block
+      if (kw0 + 31 < split && j0 + it * kQTileRows >= split) continue;
       dkdv_interior_tile(t, kf, vf, dk_acc, dv_acc);
-    } else if constexpr (RAGGED) {
-      // diagonal tile and/or partial last tile: the padding rows of a partial tile must not
-      // reach dK/dV, so every block takes the masked path (query rows >= G give P = 0);
-      // on the diagonal tile the blocks before this wave's keys are skipped
-      for (int mb = (q0 > j0 ? 0 : w); mb < 4; ++mb)
-        dkdv_block<true>(t, mb, q0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, a.G);
-    } else {
-      // diagonal tile: block mb < w is entirely before this wave's keys, block w is masked
-      dkdv_block<true>(t, w, q0 + 32 * w, key, kf, vf, dk_acc, dv_acc);
-      for (int mb = w + 1; mb < 4; ++mb) dkdv_block<false>(t, mb, 0, key, kf, vf, dk_acc, dv_acc);
+    }
+    if (has_tail && nq > 1) {
+      const DkdvTile t = begin_tile(n, hh, nq - 1);
+      const int q0 = j0 + (nq - 1) * kQTileRows;
+      for (int mb = 0; mb < 4; ++mb) dkdv_block<true>(t, mb, q0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, a.G);
+      ++n;
     }
   }
   __syncthreads();
