@@ -98,7 +98,8 @@ typedef struct s2attn_params {
    * axis is always contiguous).  All three zero = contiguous.  Lets the three slices of a
    * packed (B, N, 3, H, D) projection (Algorithm 1's qkv) be passed without a split copy:
    * {N*3*H*D, 3*H*D, D} with pointers offset by 0, H*D and 2*H*D elements.  Every stride
-   * must be a multiple of 8 elements (bf16) or 4 (fp32); o, dout, lse stay contiguous. */
+   * must be a multiple of 8 elements (bf16) or 4 (fp32) and the token stride below 2^26
+   * elements; o, dout, lse stay contiguous. */
   long long q_strides[3], k_strides[3], v_strides[3];
   long long dq_strides[3], dk_strides[3], dv_strides[3];
 } s2attn_params;

@@ -51,6 +51,7 @@ bool strides_ok(const long long (&st)[3], int B, int heads, int D, int align) {
     if (x < 0 || x % align != 0) return false;
   if (st[2] < D && heads > 1) return false;
   if (st[1] < D) return false;
+  if (st[1] >= (1LL << 26)) return false;   // kernels keep (row within a tile) * token stride in 32 bits
   if (st[0] < D && B > 1) return false;
   return true;
 }

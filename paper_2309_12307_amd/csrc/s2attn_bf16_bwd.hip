@@ -83,6 +83,18 @@ __device__ __forceinline__ void mma_acc(const bf16x8 (&buf)[8], const bf16x4 (&p
     dk_acc[db] = mfma32(buf[4 + db], dsf, dk_acc[db]);
   }
 }
+// The dP accumulator of block MB starts at delta (per query row, i.e. per register) and the
+// V fragments are negated, so that the accumulator ends as delta - dP and dS = P * -(that)
+// needs no subtraction.
+template <int MB>
+__device__ __forceinline__ void init_dp(DkdvBlock& blk, const DkdvTile& t) {
+#pragma unroll
+  for (int qtr = 0; qtr < 4; ++qtr) {
+    const float4 d4 = *reinterpret_cast<const float4*>(t.delta_s + 32 * MB + 8 * qtr + 4 * t.g32);
+    blk.dp[4 * qtr] = d4.x; blk.dp[4 * qtr + 1] = d4.y; blk.dp[4 * qtr + 2] = d4.z; blk.dp[4 * qtr + 3] = d4.w;
+  }
+}
+
 // P and dS for accumulator registers 4*QTR .. 4*QTR+3 of block MB (4 consecutive queries
 // per lane half), packed to bf16.  MASK: causal mask against this lane's key, and query
 // rows at or past q_lim (padding of a partial tile) contribute nothing.
@@ -90,8 +102,7 @@ template <int MB, int QTR, bool MASK>
 __device__ __forceinline__ void sm_quarter(const DkdvBlock& blk, const DkdvTile& t, bf16x4& pq, bf16x4& dsq,
                                            int q_first = 0, int key = 0, int q_lim = INT32_MAX) {
   const float4 l4 = *reinterpret_cast<const float4*>(t.lse2_s + 32 * MB + 8 * QTR + 4 * t.g32);
-  const float4 d4 = *reinterpret_cast<const float4*>(t.delta_s + 32 * MB + 8 * QTR + 4 * t.g32);
-  const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+  const float ls[4] = {l4.x, l4.y, l4.z, l4.w};
   float p[4], ds[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -102,7 +113,7 @@ __device__ __forceinline__ void sm_quarter(const DkdvBlock& blk, const DkdvTile&
       if (key > qrow || qrow >= q_lim) pv = 0.f;
     }
     p[e] = pv;
-    ds[e] = pv * (blk.dp[v] - dl[e]);
+    ds[e] = pv * -blk.dp[v];
   }
   pq = pack4(p[0], p[1], p[2], p[3]);
   dsq = pack4(ds[0], ds[1], ds[2], ds[3]);
@@ -122,10 +133,10 @@ __device__ __forceinline__ void dkdv_interior_tile(const DkdvTile& t, const bf16
   load_sc<0, 0>(fa, t);
   __builtin_amdgcn_sched_barrier(0);
   // 1-2: scores(0)
-  load_sc<0, 1>(fb, t); b0.s = zero16(); b0.dp = zero16(); mma_sc<0>(fa, b0, kf, vf); S2_PHASE_END(1, 0);
+  load_sc<0, 1>(fb, t); b0.s = zero16(); init_dp<0>(b0, t); mma_sc<0>(fa, b0, kf, vf); S2_PHASE_END(1, 0);
   load_sc<1, 0>(fa, t); mma_sc<1>(fb, b0, kf, vf); S2_PHASE_END(1, 0);
   // 3-4: scores(1) | softmax(0)
-  load_sc<1, 1>(fb, t); b1.s = zero16(); b1.dp = zero16(); mma_sc<0>(fa, b1, kf, vf);
+  load_sc<1, 1>(fb, t); b1.s = zero16(); init_dp<1>(b1, t); mma_sc<0>(fa, b1, kf, vf);
   sm_quarter<0, 0, false>(b0, t, pa[0], da[0]); sm_quarter<0, 1, false>(b0, t, pa[1], da[1]); S2_PHASE_END(2, 8);
   load_acc<0, 0>(fa, t); mma_sc<1>(fb, b1, kf, vf);
   sm_quarter<0, 2, false>(b0, t, pa[2], da[2]); sm_quarter<0, 3, false>(b0, t, pa[3], da[3]); S2_PHASE_END(3, 8);
@@ -133,14 +144,14 @@ __device__ __forceinline__ void dkdv_interior_tile(const DkdvTile& t, const bf16
   load_acc<0, 1>(fb, t); mma_acc<0>(fa, pa, da, dk_acc, dv_acc); sm_quarter<1, 0, false>(b1, t, pb[0], db[0]); S2_PHASE_END(3, 4);
   load_sc<2, 0>(fa, t); mma_acc<1>(fb, pa, da, dk_acc, dv_acc); sm_quarter<1, 1, false>(b1, t, pb[1], db[1]); S2_PHASE_END(2, 4);
   // 7-8: scores(2) | softmax(1) second half
-  load_sc<2, 1>(fb, t); b0.s = zero16(); b0.dp = zero16(); mma_sc<0>(fa, b0, kf, vf);
+  load_sc<2, 1>(fb, t); b0.s = zero16(); init_dp<2>(b0, t); mma_sc<0>(fa, b0, kf, vf);
   sm_quarter<1, 2, false>(b1, t, pb[2], db[2]); S2_PHASE_END(2, 4);
   load_acc<1, 0>(fa, t); mma_sc<1>(fb, b0, kf, vf); sm_quarter<1, 3, false>(b1, t, pb[3], db[3]); S2_PHASE_END(3, 4);
   // 9-10: accumulate(1) | softmax(2) first half
   load_acc<1, 1>(fb, t); mma_acc<0>(fa, pb, db, dk_acc, dv_acc); sm_quarter<2, 0, false>(b0, t, pa[0], da[0]); S2_PHASE_END(3, 4);
   load_sc<3, 0>(fa, t); mma_acc<1>(fb, pb, db, dk_acc, dv_acc); sm_quarter<2, 1, false>(b0, t, pa[1], da[1]); S2_PHASE_END(2, 4);
   // 11-12: scores(3) | softmax(2) second half
-  load_sc<3, 1>(fb, t); b1.s = zero16(); b1.dp = zero16(); mma_sc<0>(fa, b1, kf, vf);
+  load_sc<3, 1>(fb, t); b1.s = zero16(); init_dp<3>(b1, t); mma_sc<0>(fa, b1, kf, vf);
   sm_quarter<2, 2, false>(b0, t, pa[2], da[2]); S2_PHASE_END(2, 4);
   load_acc<2, 0>(fa, t); mma_sc<1>(fb, b1, kf, vf); sm_quarter<2, 3, false>(b0, t, pa[3], da[3]); S2_PHASE_END(3, 4);
   // 13-14: accumulate(2) | softmax(3) first half
@@ -167,7 +178,7 @@ __device__ __forceinline__ void dkdv_block(const DkdvTile& t, int mb, int q_firs
   bf16x8 fa[8], fb[8];
   DkdvBlock blk;
   bf16x4 pq[4], dsq[4];
-  blk.s = zero16(); blk.dp = zero16();
+  blk.s = zero16(); init_dp<0>(blk, tt);
   load_sc<0, 0>(fa, tt); load_sc<0, 1>(fb, tt);
   mma_sc<0>(fa, blk, kf, vf); mma_sc<1>(fb, blk, kf, vf);
   load_acc<0, 0>(fa, tt); load_acc<0, 1>(fb, tt);
@@ -224,23 +235,28 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
   const char* qp = static_cast<const char*>(a.q);
   const char* dop = static_cast<const char*>(a.dout);
 
-  // K^T and V^T fragments of this wave's 32 keys
+  // K^T and -V^T fragments of this wave's 32 keys (the sign: see init_dp)
   bf16x8 kf[8], vf[8];
   {
     const int tok = row_token(a, gidx, key, s);
     const bf16x8* ksrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.k) + row_off(a.sk, b, tok, c));
     const bf16x8* vsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.v) + row_off(a.sv, b, tok, c));
 #pragma unroll
-    for (int st = 0; st < 8; ++st) { kf[st] = ksrc[2 * st + g32]; vf[st] = vsrc[2 * st + g32]; }
+    for (int st = 0; st < 8; ++st) { kf[st] = ksrc[2 * st + g32]; vf[st] = -vsrc[2 * st + g32]; }
   }
 
   // staging: wave w, pass p fills tile rows 16p + 4w .. +3 (1 KB); in the aligned case
   // (shift and G multiples of 64) every 64 rows of a tile are one contiguous token run.
   const uint32_t smem_base = lds_addr(smem);
   const uint32_t rows_base = lds_addr(rows_s);
-  const size_t q_row_bytes = (size_t)a.sq.t * 2, do_row_bytes = (size_t)a.so.t * 2;
+  const uint64_t q_row_bytes = (uint64_t)a.sq.t * 2, do_row_bytes = (uint64_t)a.so.t * 2;
   const int st_row = 4 * w + (lane >> 4);
-  const size_t st_chunk = (size_t)(((lane & 15) ^ swz(st_row)) << 4);
+  const uint32_t st_chunk = (uint32_t)(((lane & 15) ^ swz(st_row)) << 4);
+  // aligned staging: scalar base of a 64-row token run plus these per-lane offsets
+  const uint32_t q_lane = (uint32_t)(st_row * q_row_bytes) + st_chunk;
+  const uint32_t do_lane = (uint32_t)(st_row * do_row_bytes) + st_chunk;
+  const uint64_t q_batch = uni64(reinterpret_cast<uint64_t>(qp) + (uint64_t)b * a.sq.b * 2);
+  const uint64_t do_batch = uni64(reinterpret_cast<uint64_t>(dop) + (uint64_t)b * a.so.b * 2);
   auto issue_tile = [&](int hh, int it, int stage) {
     const int h = h_lo + hh;
     const int q0 = (it_begin + it) * kQTileRows;
@@ -248,18 +264,18 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
       if constexpr (!RAGGED) {
-        const int tok0 = token_of(gidx * a.G + q0 + 64 * hf, s, a.N);
-        const size_t qbase = row_off(a.sq, b, tok0 + st_row, h) * 2 + st_chunk;
-        const size_t dobase = row_off(a.so, b, tok0 + st_row, h) * 2 + st_chunk;
+        const uint32_t tok0 = (uint32_t)token_of(gidx * a.G + q0 + 64 * hf, s, a.N);
+        const uint64_t qb = q_batch + tok0 * q_row_bytes + (uint64_t)h * a.sq.h * 2;
+        const uint64_t dob = do_batch + tok0 * do_row_bytes + (uint64_t)h * a.so.h * 2;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-          dma16(qp + qbase + (size_t)p * 16 * q_row_bytes, qs + (64 * hf + 16 * p) * kRowBytes);
-          dma16(dop + dobase + (size_t)p * 16 * do_row_bytes, qs + (64 * hf + 16 * p) * kRowBytes + kQTileBytes);
+          dma16s(qb + p * 16 * q_row_bytes, q_lane, qs + (64 * hf + 16 * p) * kRowBytes);
+          dma16s(dob + p * 16 * do_row_bytes, do_lane, qs + (64 * hf + 16 * p) * kRowBytes + kQTileBytes);
         }
         if (w == hf) {   // wave 0 / 1: lse and delta of rows 64*hf .. +63
-          const size_t ro = ((size_t)b * a.H + h) * a.N + tok0 + lane;
-          dma4(a.lse2 + ro, rows_base + ((stage * 2 + 0) * kQTileRows + 64 * hf) * 4);
-          dma4(a.delta + ro, rows_base + ((stage * 2 + 1) * kQTileRows + 64 * hf) * 4);
+          const uint64_t ro = (((uint64_t)b * a.H + h) * a.N + tok0) * 4;
+          dma4s(reinterpret_cast<uint64_t>(a.lse2) + ro, lane * 4, rows_base + ((stage * 2 + 0) * kQTileRows + 64 * hf) * 4);
+          dma4s(reinterpret_cast<uint64_t>(a.delta) + ro, lane * 4, rows_base + ((stage * 2 + 1) * kQTileRows + 64 * hf) * 4);
         }
       } else {   // every row finds its own token; padding rows repeat the last row of the group
 #pragma unroll

@@ -95,6 +95,25 @@ __device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
                :: "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(g) : "memory", "m0");
 }
 
+// Scalar-base form: the global address is a wave-uniform 64-bit base plus a per-lane
+// unsigned 32-bit byte offset, so that a kernel that streams tiles keeps one offset
+// register per lane and does the per-tile address arithmetic on the scalar unit.
+__device__ __forceinline__ uint64_t uni64(uint64_t u) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ void dma16s(uint64_t base, uint32_t lane_off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(lane_off), "s"(base) : "memory", "m0");
+}
+
+__device__ __forceinline__ void dma4s(uint64_t base, uint32_t lane_off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(lane_off), "s"(base) : "memory", "m0");
+}
+
 // Same with 4 bytes per lane (global_load_lds_dword): lane i lands at lds_base + 4*i.
 __device__ __forceinline__ void dma4(const void* g, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"

@@ -351,7 +351,7 @@ fwd_bf16_pp_kernel(KArgs a, int T, int n_rest) {
   const int qw0 = i0 + w * 32;
   const int qrow = qw0 + l32;
   const int jt_first = uni((i0 >= split ? split : 0) / BN);     // first tile any wave needs
-  const int nt = (i0 + BM - 1) / BN - jt_first + 1;        // tiles the workgroup walks
+  const int nt = uni((i0 + BM - 1) / BN - jt_first + 1);   // tiles the workgroup walks
   // this wave's own tile range, relative to jt_first
   const int n_lo = uni((qw0 >= split ? split : 0) / BN - jt_first);
   const int n_hi = uni((qw0 + 31) / BN - jt_first);
@@ -369,20 +369,25 @@ fwd_bf16_pp_kernel(KArgs a, int T, int n_rest) {
     for (int st = 0; st < 8; ++st) qf[st] = src[2 * st + g32];
   }
 
-  // staging: wave w, pass p fills tile rows 32p + 4w .. +3 of K and of V
+  // staging: wave w, pass p fills tile rows 32p + 4w .. +3 of K and of V.  A tile is a
+  // contiguous run of 64 tokens, so its address is a scalar (head base + first token) plus a
+  // per-lane offset (row within the pass, swizzled chunk) that never changes.
   const int st_row = 4 * w + (lane >> 4);
-  const size_t k_row_bytes = (size_t)a.sk.t * 2, v_row_bytes = (size_t)a.sv.t * 2;
+  const uint64_t k_row_bytes = (uint64_t)a.sk.t * 2, v_row_bytes = (uint64_t)a.sv.t * 2;
   const uint32_t smem_base = lds_addr(smem);
-  const size_t st_chunk = (size_t)(((lane & 15) ^ swz(st_row)) << 4);
+  const uint32_t st_chunk = (uint32_t)(((lane & 15) ^ swz(st_row)) << 4);
+  const uint32_t k_lane = (uint32_t)(st_row * k_row_bytes) + st_chunk;
+  const uint32_t v_lane = (uint32_t)(st_row * v_row_bytes) + st_chunk;
+  const uint64_t k_head = uni64(reinterpret_cast<uint64_t>(kp) + row_off(a.sk, b, 0, c) * 2);
+  const uint64_t v_head = uni64(reinterpret_cast<uint64_t>(vp) + row_off(a.sv, b, 0, c) * 2);
   auto issue_tile = [&](int n, int stage) {
-    const int tok0 = token_of(gidx * a.G + (jt_first + n) * BN, s, a.N);
-    const size_t kbase = row_off(a.sk, b, tok0 + st_row, c) * 2 + st_chunk;
-    const size_t vbase = row_off(a.sv, b, tok0 + st_row, c) * 2 + st_chunk;
+    const uint32_t tok0 = (uint32_t)token_of(gidx * a.G + (jt_first + n) * BN, s, a.N);
+    const uint64_t kb = k_head + tok0 * k_row_bytes, vb = v_head + tok0 * v_row_bytes;
     const uint32_t ks = smem_base + stage * kStageBytes + 4 * w * kRowBytes;
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
-      dma16(kp + kbase + (size_t)p * 32 * k_row_bytes, ks + 32 * p * kRowBytes);
-      dma16(vp + vbase + (size_t)p * 32 * v_row_bytes, ks + 32 * p * kRowBytes + kTileBytes);
+      dma16s(kb + p * 32 * k_row_bytes, k_lane, ks + 32 * p * kRowBytes);
+      dma16s(vb + p * 32 * v_row_bytes, v_lane, ks + 32 * p * kRowBytes + kTileBytes);
     }
   };
 

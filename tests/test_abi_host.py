@@ -88,6 +88,7 @@ def test_validator_accepts_benchmark_shapes():
     (dict(q_strides=(1024 * 4 * 128 * 3, 3 * 4 * 128, 100)), -13),    # head stride not a multiple of 8
     (dict(k_strides=(1024 * 4 * 128, -512, 128)), -13),               # negative
     (dict(dv_strides=(1024 * 4 * 128, 512, 64)), -13),                # heads would overlap
+    (dict(k_strides=((1 << 26) * 1024, 1 << 26, 128)), -13),          # token stride beyond the kernels' 32-bit row offsets
 ])
 def test_validator_codes(kw, code):
     assert binding.check_args(params(**kw), True) == code
