@@ -534,19 +534,23 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
   }
 
   const uint32_t smem_base = lds_addr(smem);
-  const size_t k_row_bytes = (size_t)a.sk.t * 2, v_row_bytes = (size_t)a.sv.t * 2;
+  const uint64_t k_row_bytes = (uint64_t)a.sk.t * 2, v_row_bytes = (uint64_t)a.sv.t * 2;
   const int st_row = 4 * w + (lane >> 4);
-  const size_t st_chunk = (size_t)(((lane & 15) ^ swz(st_row)) << 4);
+  const uint32_t st_chunk = (uint32_t)(((lane & 15) ^ swz(st_row)) << 4);
+  // aligned staging: scalar base of the tile's 64-token run plus these per-lane offsets
+  const uint32_t k_lane = (uint32_t)(st_row * k_row_bytes) + st_chunk;
+  const uint32_t v_lane = (uint32_t)(st_row * v_row_bytes) + st_chunk;
+  const uint64_t k_head = uni64(reinterpret_cast<uint64_t>(kp) + row_off(a.sk, b, 0, c) * 2);
+  const uint64_t v_head = uni64(reinterpret_cast<uint64_t>(vp) + row_off(a.sv, b, 0, c) * 2);
   auto issue_tile = [&](int jt, int stage) {
     const uint32_t ks = smem_base + stage * 2 * kTileBytes + 4 * w * kRowBytes;
     if constexpr (!RAGGED) {
-      const int tok0 = token_of(gidx * a.G + jt * BN, s, a.N);   // an aligned tile never straddles the wrap
-      const size_t kbase = row_off(a.sk, b, tok0 + st_row, c) * 2 + st_chunk;
-      const size_t vbase = row_off(a.sv, b, tok0 + st_row, c) * 2 + st_chunk;
+      const uint32_t tok0 = (uint32_t)token_of(gidx * a.G + jt * BN, s, a.N);   // an aligned tile never straddles the wrap
+      const uint64_t kb = k_head + tok0 * k_row_bytes, vb = v_head + tok0 * v_row_bytes;
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
-        dma16(kp + kbase + (size_t)p * 16 * k_row_bytes, ks + 16 * p * kRowBytes);
-        dma16(vp + vbase + (size_t)p * 16 * v_row_bytes, ks + 16 * p * kRowBytes + kTileBytes);
+        dma16s(kb + p * 16 * k_row_bytes, k_lane, ks + 16 * p * kRowBytes);
+        dma16s(vb + p * 16 * v_row_bytes, v_lane, ks + 16 * p * kRowBytes + kTileBytes);
       }
     } else {   // every row finds its own token; padding rows repeat the last row of the group
 #pragma unroll
