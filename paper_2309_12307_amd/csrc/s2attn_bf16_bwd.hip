@@ -607,6 +607,9 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
 }  // namespace
 
 int launch_bwd_dkdv_bf16(const KArgs& a, hipStream_t st) {
+#ifndef S2X_NO_SPLIT
+  if (dkdv_split_applies(a)) return launch_bwd_dkdv_split_bf16(a, st);
+#endif
   const int NG = a.N / a.G;
   const int ncls = a.mixed ? 2 : 1;
   const int T = (a.G + 127) / 128;

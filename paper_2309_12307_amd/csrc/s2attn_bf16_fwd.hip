@@ -433,7 +433,10 @@ fwd_bf16_pp_kernel(KArgs a, int T, int n_rest) {
     const char* Ks_nxt = smem + st_nxt * kStageBytes;
     const char* Vs_nxt = Ks_nxt + kTileBytes;
     if (grp == 1 && act) fwd_softmax(st, s0, s1, c2, pf);
-    // Every step issues the LDS reads of the step two ahead, then its own four MFMAs.
+    // Every step issues the LDS reads of the step two ahead, then its own four MFMAs.  The
+    // matrix block runs at raised priority so that it is not starved by the vector work of
+    // the wave it shares the SIMD with.
+    __builtin_amdgcn_s_setprio(1);
     if (act) {
       pp_load<2>(ring[2], Vs_cur, Ks_nxt, lo);
       pp_mma<0>(ring[0], st, pf, qf, s0, s1);
@@ -467,10 +470,12 @@ fwd_bf16_pp_kernel(KArgs a, int T, int n_rest) {
       pp_load<1>(ring[1], Vs_nxt, nullptr, lo);
       pp_mma<7>(ring[3], st, pf, qf, s0, s1);
       __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(0);
       const int j0 = (jt_first + n + 1) * BN;
       if (j0 + BN - 1 > qw0) mask_scores(s0, s1, j0, qrow, g32);
       if (grp == 0) fwd_softmax(st, s0, s1, c2, pf);
     }
+    __builtin_amdgcn_s_setprio(0);
     const int t = st_cur; st_cur = st_nxt; st_nxt = st_free; st_free = t;
   }
   __syncthreads();
