@@ -58,14 +58,15 @@ __device__ __forceinline__ void sc_mma(const bf16x8 (&buf)[4], const bf16x8 (&bf
 }
 __device__ __forceinline__ void scores(f32x16& acc0, f32x16& acc1, const char* Xs, const LaneOffsets& lo,
                                        const bf16x8 (&bf)[8]) {
-  bf16x8 fa[4], fb[4];
+  bf16x8 fa[4], fb[4], fc[4];
   sc_load<0>(fa, Xs, lo);
+  sc_load<1>(fb, Xs, lo);
   __builtin_amdgcn_sched_barrier(0);
   __builtin_amdgcn_s_setprio(1);   // matrix work goes ahead of the other wave's vector work
-  sc_load<1>(fb, Xs, lo); sc_mma<0>(fa, bf, acc0, acc1); __builtin_amdgcn_sched_barrier(0);
-  sc_load<2>(fa, Xs, lo); sc_mma<1>(fb, bf, acc0, acc1); __builtin_amdgcn_sched_barrier(0);
-  sc_load<3>(fb, Xs, lo); sc_mma<2>(fa, bf, acc0, acc1); __builtin_amdgcn_sched_barrier(0);
-  sc_mma<3>(fb, bf, acc0, acc1);
+  sc_load<2>(fc, Xs, lo); sc_mma<0>(fa, bf, acc0, acc1); __builtin_amdgcn_sched_barrier(0);
+  sc_load<3>(fa, Xs, lo); sc_mma<1>(fb, bf, acc0, acc1); __builtin_amdgcn_sched_barrier(0);
+  sc_mma<2>(fc, bf, acc0, acc1); __builtin_amdgcn_sched_barrier(0);
+  sc_mma<3>(fa, bf, acc0, acc1);
   __builtin_amdgcn_s_setprio(0);
   __builtin_amdgcn_sched_barrier(0);
 }
@@ -81,15 +82,15 @@ __device__ __forceinline__ void ac_mma(const bf16x8 (&buf)[4], bf16x8 wf, f32x16
 #pragma unroll
   for (int db = 0; db < 4; ++db) acc[db] = mfma32(buf[db], wf, acc[db]);
 }
-// `fa` already holds the fragments of step 0.
-__device__ __forceinline__ void accumulate(f32x16 (&acc)[4], bf16x8 (&fa)[4], const char* Xs, const LaneOffsets& lo,
-                                           const bf16x8 (&wf)[4]) {
-  bf16x8 fb[4];
+// `fa` and `fb` already hold the fragments of steps 0 and 1 (loaded ahead of the vector work).
+__device__ __forceinline__ void accumulate(f32x16 (&acc)[4], bf16x8 (&fa)[4], bf16x8 (&fb)[4], const char* Xs,
+                                           const LaneOffsets& lo, const bf16x8 (&wf)[4]) {
+  bf16x8 fc[4];
   __builtin_amdgcn_s_setprio(1);
-  ac_load<1>(fb, Xs, lo); ac_mma(fa, wf[0], acc); __builtin_amdgcn_sched_barrier(0);
-  ac_load<2>(fa, Xs, lo); ac_mma(fb, wf[1], acc); __builtin_amdgcn_sched_barrier(0);
-  ac_load<3>(fb, Xs, lo); ac_mma(fa, wf[2], acc); __builtin_amdgcn_sched_barrier(0);
-  ac_mma(fb, wf[3], acc);
+  ac_load<2>(fc, Xs, lo); ac_mma(fa, wf[0], acc); __builtin_amdgcn_sched_barrier(0);
+  ac_load<3>(fa, Xs, lo); ac_mma(fb, wf[1], acc); __builtin_amdgcn_sched_barrier(0);
+  ac_mma(fc, wf[2], acc); __builtin_amdgcn_sched_barrier(0);
+  ac_mma(fa, wf[3], acc);
   __builtin_amdgcn_s_setprio(0);
   __builtin_amdgcn_sched_barrier(0);
 }
@@ -208,8 +209,9 @@ bwd_dkdv_split_kernel(KArgs a, int T, int n_rest) {
             lr[mb][vv] = *reinterpret_cast<const float4*>(lse2_s + 32 * mb + 8 * vv + 4 * g32);
         f32x16 s0 = zero16(), s1 = zero16();
         scores(s0, s1, Qs, lo, bfrag);
-        bf16x8 fa[4];
+        bf16x8 fa[4], fb[4];
         ac_load<0>(fa, dOs, lo);       // first dO^T fragments arrive during the vector work
+        ac_load<1>(fb, dOs, lo);
         bf16x8 pf[4];
         auto softmax_block = [&](auto masked_c, int mb, f32x16& sx) {
           constexpr bool MASKED = decltype(masked_c)::value;
@@ -236,7 +238,7 @@ bwd_dkdv_split_kernel(KArgs a, int T, int n_rest) {
           softmax_block(std::false_type{}, 1, s1);
         }
         __builtin_amdgcn_sched_barrier(0);
-        accumulate(acc, fa, dOs, lo, pf);
+        accumulate(acc, fa, fb, dOs, lo, pf);
       }
       if (++it == nq) it = 0;
       q_st = q_st == 2 ? 0 : q_st + 1;
@@ -255,7 +257,7 @@ bwd_dkdv_split_kernel(KArgs a, int T, int n_rest) {
       }
       const bool has_prev = n >= 1, has_cur = n < n_iter;
       const char* Qs = smem + kOffQ + (q_st == 0 ? 2 : q_st - 1) * kQTBytes;   // tile n-1
-      bf16x8 fa[4], dsf[4];
+      bf16x8 fa[4], fb[4], dsf[4];
       if (has_prev) {
         // finish tile n-1: dS = P * (dP - delta)
         const char* Px = smem + kOffP + (o_st ^ 1) * kPBufBytes + kb * 2 * kPBlockBytes + lane * 16;
@@ -266,6 +268,7 @@ bwd_dkdv_split_kernel(KArgs a, int T, int n_rest) {
           for (int vv = 0; vv < 4; ++vv)
             pr[mb][vv] = *reinterpret_cast<const float4*>(Px + mb * kPBlockBytes + vv * 1024);
         ac_load<0>(fa, Qs, lo);
+        ac_load<1>(fb, Qs, lo);
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
           f32x16& dx = mb == 0 ? dp0 : dp1;
@@ -294,7 +297,7 @@ bwd_dkdv_split_kernel(KArgs a, int T, int n_rest) {
         }
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (has_prev) accumulate(acc, fa, Qs, lo, dsf);   // dK^T += Q^T dS
+      if (has_prev) accumulate(acc, fa, fb, Qs, lo, dsf);   // dK^T += Q^T dS
       if (has_cur) scores(dp0, dp1, smem + kOffdO + o_st * kQTBytes, lo, bfrag);
       q_st = q_st == 2 ? 0 : q_st + 1;
     }
