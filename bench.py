@@ -28,7 +28,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 # scaled by a 1 GiB copy probe (profiles/s2attn_fwd_bwd_C3_rocprofv3.md), keyed by workload
 # then kernel.  Not measurable from inside the process; null for workloads not profiled.
 MEASURED_TRAFFIC = {
-    "C3": {"fwd": 1.710e9, "bwd_dkdv": 2.297e9, "bwd_dq": 2.515e9},
+    "C3": {"fwd": 1.838e9, "bwd_dkdv": 2.472e9, "bwd_dq": 2.569e9},
 }
 
 
