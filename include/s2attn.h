@@ -45,7 +45,7 @@ enum {
   S2ATTN_ERR_ALIGN = -2,       /* a tensor pointer is not 16-byte aligned */
   S2ATTN_ERR_DIM = -3,         /* B, N, H, Hkv, D or G is not positive */
   S2ATTN_ERR_GROUP = -4,       /* N % G != 0, or G odd, or shift outside [0, G) */
-  S2ATTN_ERR_HEADS = -5,       /* H odd (half of the heads shift), or H % Hkv != 0 */
+  S2ATTN_ERR_HEADS = -5,       /* H odd (half of the heads shift), H % Hkv != 0, or inconsistent head sharding */
   S2ATTN_ERR_HEADDIM = -6,     /* D not supported: fp32 needs D in {64,128}; bf16 needs D == 128 */
   S2ATTN_ERR_TILE = -7,        /* bf16 path with S2ATTN_WRAP_SPLIT: G must be a multiple of 128 and shift of 64
                                   (S2ATTN_WRAP_JOINT takes any even G and any shift; multiples of 128 / 64
@@ -102,6 +102,14 @@ typedef struct s2attn_params {
    * elements; o, dout, lse stay contiguous. */
   long long q_strides[3], k_strides[3], v_strides[3];
   long long dq_strides[3], dk_strides[3], dv_strides[3];
+  /* Head-sharded use (one GPU holds heads [head_offset, head_offset + H) of a layer with
+   * heads_total query heads): under S2ATTN_SHIFT_SECOND_HALF the shifted heads are those whose
+   * layer-wide index is >= heads_total / 2.  heads_total == 0 (the default) means the call
+   * sees the whole layer (heads_total = H, head_offset = 0).  heads_total must be even,
+   * head_offset + H <= heads_total and head_offset a multiple of H / Hkv; H itself may then
+   * be odd. */
+  int heads_total;
+  int head_offset;
 } s2attn_params;
 
 /* Pure host check of a parameter block (pointers, alignment, shapes, workspace
@@ -112,6 +120,10 @@ S2ATTN_API int s2attn_check_args(const s2attn_params* p, int backward);
  * delta[b,h,t] = sum_d dout*o and a base-2 copy of lse, plus fp32 partial dk/dv when a kv head serves both
  * shifted and unshifted query heads (odd Hkv under the second-half rule). */
 S2ATTN_API size_t s2attn_bwd_workspace_bytes(int B, int N, int H, int Hkv, int D, int G, int dtype);
+
+/* Same for a parameter block (accounts for its shift rule and head sharding, which decide
+ * whether a kv head serves both kinds of query heads); 0 if the shape fields are invalid. */
+S2ATTN_API size_t s2attn_bwd_workspace_bytes_ex(const s2attn_params* p);
 
 /* Forward of Algorithm 1, bf16 tensors, fp32 accumulation, default shift G/2 on
  * heads [H/2, H), scale 1/sqrt(D). */

@@ -21,6 +21,7 @@ EXPORTS = [
     "s2attn_check_args", "s2attn_bwd_workspace_bytes", "s2attn_fwd", "s2attn_bwd",
     "s2attn_fwd_f32", "s2attn_bwd_f32", "s2attn_fwd_ex", "s2attn_bwd_ex",
     "s2attn_strerror", "s2attn_effective_flops", "s2attn_bwd_ex_marked",
+    "s2attn_bwd_workspace_bytes_ex",
 ]
 
 
@@ -37,6 +38,7 @@ class S2AttnParams(ctypes.Structure):
         ("q_strides", ctypes.c_longlong * 3), ("k_strides", ctypes.c_longlong * 3),
         ("v_strides", ctypes.c_longlong * 3), ("dq_strides", ctypes.c_longlong * 3),
         ("dk_strides", ctypes.c_longlong * 3), ("dv_strides", ctypes.c_longlong * 3),
+        ("heads_total", ctypes.c_int), ("head_offset", ctypes.c_int),
     ]
 
 
@@ -63,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.s2attn_check_args.restype = i
         L.s2attn_bwd_workspace_bytes.argtypes = [i] * 7
         L.s2attn_bwd_workspace_bytes.restype = sz
+        L.s2attn_bwd_workspace_bytes_ex.argtypes = [ctypes.POINTER(S2AttnParams)]
+        L.s2attn_bwd_workspace_bytes_ex.restype = sz
         for name in ("s2attn_fwd", "s2attn_fwd_f32"):
             f = getattr(L, name)
             f.argtypes = [vp] * 5 + [i] * 6 + [vp]
@@ -134,13 +138,18 @@ def bwd_workspace_bytes(B, N, H, Hkv, D, G, dtype=BF16) -> int:
     return int(lib().s2attn_bwd_workspace_bytes(B, N, H, Hkv, D, G, dtype))
 
 
+def bwd_workspace_bytes_ex(p: "S2AttnParams") -> int:
+    """Workspace size for a parameter block (accounts for its shift rule and head sharding)."""
+    return int(lib().s2attn_bwd_workspace_bytes_ex(ctypes.byref(p)))
+
+
 def effective_flops(B, N, H, D, G, which: int = 2) -> float:
     return float(lib().s2attn_effective_flops(B, N, H, D, G, which))
 
 
 def make_params(q, k, v, o, lse, G, dout=None, dq=None, dk=None, dv=None, workspace=None,
                 shift=-1, shift_rule=SHIFT_SECOND_HALF, wrap_variant=WRAP_JOINT, scale=0.0,
-                dtype=None, dims=None, strided=False) -> S2AttnParams:
+                dtype=None, dims=None, strided=False, heads_total=0, head_offset=0) -> S2AttnParams:
     """strided=True takes the {batch, token, head} strides of q, k, v (and dq, dk, dv) from
     the tensors themselves, so views into a packed (B, N, 3, H, D) tensor can be passed."""
     if dims is None:
@@ -155,6 +164,7 @@ def make_params(q, k, v, o, lse, G, dout=None, dq=None, dk=None, dv=None, worksp
     p.B, p.N, p.H, p.Hkv, p.D, p.G = B, N, H, Hkv, D, G
     p.dtype = _dtype_code(q) if dtype is None else dtype
     p.shift, p.shift_rule, p.wrap_variant, p.scale = shift, shift_rule, wrap_variant, scale
+    p.heads_total, p.head_offset = heads_total, head_offset
     if strided:
         for name, t in (("q", q), ("k", k), ("v", v), ("dq", dq), ("dk", dk), ("dv", dv)):
             if t is None or isinstance(t, int):

@@ -4,6 +4,7 @@
 #include "s2attn.h"
 
 #include <atomic>
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 
@@ -20,13 +21,20 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 // First head that uses the shifted partition under a rule (Algorithm 1 shifts the
 // second chunk of chunk(2, head axis)).
-int shifted_from(int rule, int H, int shift) {
+int shifted_from(int rule, int H, int shift, int heads_total = 0, int head_offset = 0) {
   if (shift == 0) return H;
   switch (rule) {
-    case S2ATTN_SHIFT_SECOND_HALF: return H / 2;
+    case S2ATTN_SHIFT_SECOND_HALF:
+      // head-sharded: local index of the layer's head heads_total / 2, clamped to this shard
+      if (heads_total > 0) return std::min(std::max(heads_total / 2 - head_offset, 0), H);
+      return H / 2;
     case S2ATTN_SHIFT_NONE: return H;
     default: return 0;
   }
+}
+
+int shifted_from(const s2attn_params* p, int shift) {
+  return shifted_from(p->shift_rule, p->H, shift, p->heads_total, p->head_offset);
 }
 
 int resolved_shift(const s2attn_params* p) { return p->shift < 0 ? p->G / 2 : p->shift; }
@@ -65,7 +73,14 @@ int check_common(const s2attn_params* p, int backward) {
   if (p->N % p->G != 0 || p->G % 2 != 0) return S2ATTN_ERR_GROUP;
   const int shift = resolved_shift(p);
   if (shift < 0 || shift >= p->G) return S2ATTN_ERR_GROUP;
-  if (p->H % 2 != 0 || p->H % p->Hkv != 0) return S2ATTN_ERR_HEADS;
+  if (p->H % p->Hkv != 0) return S2ATTN_ERR_HEADS;
+  if (p->heads_total == 0) {
+    if (p->H % 2 != 0 || p->head_offset != 0) return S2ATTN_ERR_HEADS;
+  } else {
+    if (p->heads_total < 0 || p->heads_total % 2 != 0 || p->head_offset < 0 ||
+        (long long)p->head_offset + p->H > p->heads_total || p->head_offset % (p->H / p->Hkv) != 0)
+      return S2ATTN_ERR_HEADS;
+  }
   if (p->dtype == S2ATTN_F32) {
     if (p->D != 64 && p->D != 128) return S2ATTN_ERR_HEADDIM;
   } else {
@@ -98,7 +113,7 @@ int check_common(const s2attn_params* p, int backward) {
       if (!x) return S2ATTN_ERR_NULL;
       if (!aligned16(x)) return S2ATTN_ERR_ALIGN;
     }
-    const bool mixed = kv_heads_mixed(p->H, p->Hkv, shifted_from(p->shift_rule, p->H, shift));
+    const bool mixed = kv_heads_mixed(p->H, p->Hkv, shifted_from(p, shift));
     const size_t need = workspace_bytes_for(p->B, p->N, p->H, p->Hkv, p->D, mixed);
     if (!p->workspace || p->workspace_bytes < need) return S2ATTN_ERR_WORKSPACE;
     if ((reinterpret_cast<uintptr_t>(p->workspace) & (kAlign - 1)) != 0) return S2ATTN_ERR_ALIGN;
@@ -149,7 +164,7 @@ s2::KArgs make_kargs(const s2attn_params* p) {
   const long long zero3[3] = {0, 0, 0};
   a.so = resolve_strides(zero3, p->N, p->H, p->D);
   a.shift = resolved_shift(p);
-  a.shifted_from = shifted_from(p->shift_rule, p->H, a.shift);
+  a.shifted_from = shifted_from(p, a.shift);
   a.split = (p->wrap_variant == S2ATTN_WRAP_SPLIT && a.shift > 0) ? p->G - a.shift : p->G;
   a.mixed = kv_heads_mixed(p->H, p->Hkv, a.shifted_from) ? 1 : 0;
   a.ragged = (p->dtype == S2ATTN_BF16 && (p->G % 128 != 0 || a.shift % 64 != 0)) ? 1 : 0;
@@ -184,6 +199,13 @@ size_t s2attn_bwd_workspace_bytes(int B, int N, int H, int Hkv, int D, int G, in
   // sized for the default rule; the other rules never mix classes inside a kv head
   const bool mixed = kv_heads_mixed(H, Hkv, H / 2);
   return workspace_bytes_for(B, N, H, Hkv, D, mixed);
+}
+
+size_t s2attn_bwd_workspace_bytes_ex(const s2attn_params* p) {
+  if (!p || p->B <= 0 || p->N <= 0 || p->H <= 0 || p->Hkv <= 0 || p->D <= 0 || p->G <= 0 || p->H % p->Hkv != 0)
+    return 0;
+  const bool mixed = kv_heads_mixed(p->H, p->Hkv, shifted_from(p, resolved_shift(p)));
+  return workspace_bytes_for(p->B, p->N, p->H, p->Hkv, p->D, mixed);
 }
 
 int s2attn_fwd_ex(const s2attn_params* p, void* stream) {

@@ -83,3 +83,34 @@ def run_hip_packed(inp: dict, G: int, dtype: str, **ex):
     binding.s2attn_bwd_ex(p)
     torch.cuda.synchronize()
     return dict(o=to_np(o), lse=to_np(lse), dq=to_np(dq), dk=to_np(dk), dv=to_np(dv))
+
+
+def run_hip_head_shard(inp: dict, G: int, dtype: str, h0: int, h1: int, **ex):
+    """Runs heads [h0, h1) of the layer in `inp` as one head shard: q, k, v are strided views
+    of the layer's tensors (kv heads [h0/r, h1/r)), the shard's position in the layer goes
+    through heads_total / head_offset.  Returns the shard's o, lse, dq, dk, dv."""
+    bf = dtype == "bf16"
+    q = to_dev(inp["q"], inp.get("q_bits") if bf else None)
+    k = to_dev(inp["k"], inp.get("k_bits") if bf else None)
+    v = to_dev(inp["v"], inp.get("v_bits") if bf else None)
+    do = to_dev(inp["do"], inp.get("do_bits") if bf else None)
+    B, N, H, D = q.shape
+    r = H // k.shape[2]
+    assert h0 % r == 0 and h1 % r == 0
+    qv, kv, vv = q[:, :, h0:h1], k[:, :, h0 // r:h1 // r], v[:, :, h0 // r:h1 // r]
+    dov = do[:, :, h0:h1].contiguous()
+    Hs, Hkvs = h1 - h0, (h1 - h0) // r
+    o = torch.full((B, N, Hs, D), float("nan"), dtype=q.dtype, device="cuda")
+    lse = torch.full((B, Hs, N), float("nan"), dtype=torch.float32, device="cuda")
+    dq = torch.full_like(o, float("nan"))
+    dk = torch.full((B, N, Hkvs, D), float("nan"), dtype=q.dtype, device="cuda")
+    dv = torch.full_like(dk, float("nan"))
+    kw = dict(strided=True, heads_total=H, head_offset=h0, dims=(B, N, Hs, Hkvs, D), **ex)
+    p = binding.make_params(qv, kv, vv, o, lse, G, **kw)
+    binding.s2attn_fwd_ex(p)
+    p = binding.make_params(qv, kv, vv, o, lse, G, dout=dov, dq=dq, dk=dk, dv=dv, **kw)
+    ws = torch.empty(binding.bwd_workspace_bytes_ex(p), dtype=torch.uint8, device="cuda")
+    p = binding.make_params(qv, kv, vv, o, lse, G, dout=dov, dq=dq, dk=dk, dv=dv, workspace=ws, **kw)
+    binding.s2attn_bwd_ex(p)
+    torch.cuda.synchronize()
+    return dict(o=to_np(o), lse=to_np(lse), dq=to_np(dq), dk=to_np(dk), dv=to_np(dv))

@@ -53,6 +53,8 @@ def params(**kw):
     p.shift_rule = kw.get("shift_rule", 0)
     p.wrap_variant = kw.get("wrap_variant", 0)
     p.scale = 0.0
+    p.heads_total = kw.get("heads_total", 0)
+    p.head_offset = kw.get("head_offset", 0)
     return p
 
 
@@ -103,6 +105,35 @@ def test_validator_codes(kw, code):
 ])
 def test_validator_accepts_unaligned_groups_in_bf16(kw):
     assert binding.check_args(params(**kw), True) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(H=3, Hkv=3, heads_total=12, head_offset=3), 0),     # an odd shard of a 12-head layer
+    (dict(H=4, Hkv=2, heads_total=16, head_offset=6), 0),     # shard straddles the layer's middle
+    (dict(H=4, Hkv=2, heads_total=16, head_offset=5), -5),    # offset splits a kv head's query heads
+    (dict(H=4, Hkv=4, heads_total=15, head_offset=0), -5),    # the layer's head count must be even
+    (dict(H=4, Hkv=4, heads_total=6, head_offset=4), -5),     # shard runs past the layer
+    (dict(H=4, Hkv=4, heads_total=8, head_offset=-4), -5),
+    (dict(H=4, Hkv=4, head_offset=4), -5),                    # offset without a layer size
+])
+def test_head_sharding_fields(kw, code):
+    assert binding.check_args(params(**kw), True) == code
+
+
+def test_workspace_size_follows_the_shard():
+    # heads 6..9 of a 16-head layer with 2 query heads per kv head: local heads 2, 3 shift,
+    # every kv head is wholly on one side -> no partial sums
+    p = params(H=4, Hkv=2, heads_total=16, head_offset=6)
+    assert binding.bwd_workspace_bytes_ex(p) == 2 * 4 * 1024 * 4
+    # heads 4..11 with 4 query heads per kv head: the layer's middle (head 8) is local head 4,
+    # a kv-head boundary -> still none; with heads_total = 20 the middle is local head 6 -> mixed
+    p = params(H=8, Hkv=2, heads_total=16, head_offset=4)
+    assert binding.bwd_workspace_bytes_ex(p) == 2 * 8 * 1024 * 4
+    p = params(H=8, Hkv=2, heads_total=20, head_offset=4)
+    assert binding.bwd_workspace_bytes_ex(p) == 2 * 8 * 1024 * 4 + 4 * 1024 * 2 * 128 * 4
+    # whole layer: same as the plain query
+    p = params()
+    assert binding.bwd_workspace_bytes_ex(p) == binding.bwd_workspace_bytes(1, 1024, 4, 4, 128, 256)
 
 
 def test_packed_qkv_strides_are_accepted():

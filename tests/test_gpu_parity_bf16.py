@@ -178,6 +178,23 @@ def test_unaligned_group_packed_qkv_views():
     compare(out, ref)
 
 
+@pytest.mark.parametrize("layer,shards", [
+    ((1, 1024, 8, 4, 128, 256), [(0, 4), (4, 8), (2, 6)]),
+    ((1, 768, 12, 3, 128, 256), [(4, 8)]),          # the layer's middle splits the shard's kv head
+    ((1, 1000, 8, 8, 128, 500), [(3, 8)]),          # unaligned group, odd shard
+])
+def test_head_shards_reproduce_the_layer(layer, shards):
+    from gpu_util import run_hip_head_shard
+    B, N, H, Hkv, D, G = layer
+    r = H // Hkv
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=500 + sum(layer), dtype="bf16")
+    o, lse, dq, dk, dv = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G)
+    for h0, h1 in shards:
+        out = run_hip_head_shard(inp, G, "bf16", h0, h1)
+        compare(out, (o[:, :, h0:h1], lse[:, h0:h1], dq[:, :, h0:h1], dk[:, :, h0 // r:h1 // r],
+                      dv[:, :, h0 // r:h1 // r]))
+
+
 def test_outputs_are_deterministic():
     from gpu_util import run_hip
     inp = inputs.make_inputs(1, 1024, 4, 2, 128, seed=5, dtype="bf16")

@@ -116,3 +116,30 @@ def test_outputs_are_deterministic():
     b = run_hip(inp, cfg.G, "f32")
     for name in a:
         assert np.array_equal(a[name], b[name]), name
+
+
+# (layer: B, N, H, Hkv, D, G), shards as head ranges.  Each shard must reproduce its slice of
+# the whole layer's result: the shifted heads are those >= H/2 of the LAYER, wherever the
+# shard boundary falls (all shifted, none shifted, or the layer's middle inside the shard,
+# also inside a kv head's query heads).
+SHARDINGS = [
+    ((1, 256, 8, 4, 64, 64), [(0, 4), (4, 8)]),
+    ((1, 256, 8, 4, 64, 64), [(0, 2), (2, 8)]),
+    ((2, 200, 12, 3, 64, 100), [(0, 4), (4, 8), (8, 12)]),   # middle head 6 splits kv head 1
+    ((1, 256, 6, 6, 128, 128), [(0, 3), (3, 6), (1, 6)]),     # odd shards
+]
+
+
+@pytest.mark.parametrize("layer,shards", SHARDINGS)
+def test_head_shards_reproduce_the_layer(layer, shards):
+    from gpu_util import run_hip_head_shard
+    B, N, H, Hkv, D, G = layer
+    r = H // Hkv
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=400 + sum(layer), dtype="f32")
+    o, lse, dq, dk, dv = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G)
+    # dk, dv of a kv head depend only on its own query heads, so a shard made of whole kv
+    # heads reproduces them as well
+    for h0, h1 in shards:
+        out = run_hip_head_shard(inp, G, "f32", h0, h1)
+        ref = (o[:, :, h0:h1], lse[:, h0:h1], dq[:, :, h0:h1], dk[:, :, h0 // r:h1 // r], dv[:, :, h0 // r:h1 // r])
+        compare(out, ref)
