@@ -136,6 +136,9 @@ RAGGED_SHAPES = [
     (1, 1000, 2, 2, 128, 1000),    # one group; last wave of the last tile is all padding
     (1, 1290, 6, 3, 128, 258),     # two-row tail; odd Hkv: middle kv head is mixed
     (1, 10000, 2, 2, 128, 2500),   # N = 100000, G = 25000 (Section 4.2) scaled down by 10
+    (1, 4, 2, 2, 128, 2),          # smallest group: two tokens, shift 1
+    (1, 24, 2, 1, 128, 6),
+    (1, 130, 2, 2, 128, 130),      # one group whose second tile holds two rows
 ]
 
 
