@@ -195,7 +195,7 @@ __device__ __forceinline__ void dkdv_block(const DkdvTile& t, int mb, int q_firs
 // padding rows of the last tile are masked.  The aligned instantiation carries none of it.
 template <bool RAGGED>
 __global__ void __launch_bounds__(256, 1)
-bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
+bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
   __shared__ __attribute__((aligned(1024))) char smem[4 * kQTileBytes];            // [stage][Q,dO]
   __shared__ __attribute__((aligned(1024))) float rows_s[2][2][kQTileRows];        // [stage][lse * log2(e), delta]
 
@@ -204,8 +204,8 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int n_rest) {
 
   // block -> (batch, kv head, class, group, key tile); heaviest key tiles (jt = 0) first
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int y = uni(slot / T);
-  const int jt = slot - y * T;
+  int y, jt;
+  decode_slot(slot, T, il, y, jt);
   int rest = uni(y * 8 + xcd);
   if (rest >= n_rest) return;
   const int NG = uni(a.N / a.G);
@@ -488,7 +488,7 @@ __device__ __forceinline__ void dq_tile(f32x16 (&dq_acc)[4], const bf16x8 (&qf)[
 
 template <bool RAGGED>
 __global__ void __launch_bounds__(256, 2)
-bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
+bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   constexpr int BM = 128;
   __shared__ __attribute__((aligned(1024))) char smem[4 * kTileBytes];   // [stage][K,V]
 
@@ -496,8 +496,9 @@ bwd_dq_bf16_kernel(KArgs a, int T, int n_rest) {
   const int g32 = lane >> 5, l32 = lane & 31;
 
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int y = uni(slot / T);
-  const int qt = T - 1 - (slot - y * T);
+  int y, rank;
+  decode_slot(slot, T, il, y, rank);
+  const int qt = T - 1 - rank;
   const int hr = uni(y % a.r);
   int rest = uni(uni(y / a.r) * 8 + xcd);
   if (rest >= n_rest) return;
@@ -614,11 +615,12 @@ int launch_bwd_dkdv_bf16(const KArgs& a, hipStream_t st) {
   const int ncls = a.mixed ? 2 : 1;
   const int T = (a.G + 127) / 128;
   const int n_rest = a.B * a.Hkv * ncls * NG;
-  const int blocks = 8 * T * ((n_rest + 7) / 8);
+  const int il = interleave_for(T, 32);   // 32 CUs per XCD, one workgroup each
+  const int blocks = 8 * T * pad_to((n_rest + 7) / 8, il);
   if (a.ragged)
-    hipLaunchKernelGGL(bwd_dkdv_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, ncls, T, n_rest);
+    hipLaunchKernelGGL(bwd_dkdv_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, ncls, T, il, n_rest);
   else
-    hipLaunchKernelGGL(bwd_dkdv_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, ncls, T, n_rest);
+    hipLaunchKernelGGL(bwd_dkdv_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, ncls, T, il, n_rest);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -626,11 +628,12 @@ int launch_bwd_dq_bf16(const KArgs& a, hipStream_t st) {
   const int NG = a.N / a.G;
   const int T = (a.G + 127) / 128;
   const int n_rest = a.B * a.Hkv * NG;
-  const int blocks = 8 * T * a.r * ((n_rest + 7) / 8);
+  const int il = interleave_for(T, 64);   // 32 CUs per XCD, two workgroups each
+  const int blocks = 8 * T * pad_to(a.r * ((n_rest + 7) / 8), il);
   if (a.ragged)
-    hipLaunchKernelGGL(bwd_dq_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
+    hipLaunchKernelGGL(bwd_dq_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, T, il, n_rest);
   else
-    hipLaunchKernelGGL(bwd_dq_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
+    hipLaunchKernelGGL(bwd_dq_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, T, il, n_rest);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -96,7 +96,7 @@ __device__ __forceinline__ void accumulate(f32x16 (&acc)[4], bf16x8 (&fa)[4], bf
 }
 
 __global__ void __launch_bounds__(512, 1)
-bwd_dkdv_split_kernel(KArgs a, int T, int n_rest) {
+bwd_dkdv_split_kernel(KArgs a, int T, int il, int n_rest) {
   __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
 
   const int tid = threadIdx.x, lane = tid & 63, w = uni(tid >> 6);
@@ -106,8 +106,8 @@ bwd_dkdv_split_kernel(KArgs a, int T, int n_rest) {
 
   // block -> (batch, kv head, group, key tile); heaviest key tiles (jt = 0) first
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int y = uni(slot / T);
-  const int jt = uni(slot - y * T);
+  int y, jt;
+  decode_slot(slot, T, il, y, jt);
   int rest = uni(y * 8 + xcd);
   if (rest >= n_rest) return;
   const int NG = uni(a.N / a.G);
@@ -329,8 +329,9 @@ int launch_bwd_dkdv_split_bf16(const KArgs& a, hipStream_t st) {
   const int NG = a.N / a.G;
   const int T = a.G / 128;
   const int n_rest = a.B * a.Hkv * NG;
-  const int blocks = 8 * T * ((n_rest + 7) / 8);
-  hipLaunchKernelGGL(bwd_dkdv_split_kernel, dim3(blocks), dim3(512), 0, st, a, T, n_rest);
+  const int il = interleave_for(T, 32);   // 32 CUs per XCD, one workgroup each
+  const int blocks = 8 * T * pad_to((n_rest + 7) / 8, il);
+  hipLaunchKernelGGL(bwd_dkdv_split_kernel, dim3(blocks), dim3(512), 0, st, a, T, il, n_rest);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -168,7 +168,7 @@ __device__ __forceinline__ void fwd_epilogue(const KArgs& a, FwdState& st, char*
 // the wrap point may fall inside one, so every staged row finds its own token.
 template <bool RAGGED>
 __global__ void __launch_bounds__(256, 2)
-fwd_bf16_kernel(KArgs a, int T, int n_rest) {
+fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   constexpr int BM = 128;
   __shared__ __attribute__((aligned(1024))) char smem[4 * kTileBytes];   // [stage][K,V]
 
@@ -181,8 +181,9 @@ fwd_bf16_kernel(KArgs a, int T, int n_rest) {
   // all query tiles (heaviest first) of a triple back to back, so that the K/V of a
   // group stay in that XCD's L2 while they are being re-read.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int y = uni(slot / T);
-  const int qt = T - 1 - (slot - y * T);
+  int y, rank;
+  decode_slot(slot, T, il, y, rank);
+  const int qt = T - 1 - rank;
   const int hr = uni(y % a.r);
   int rest = uni(uni(y / a.r) * 8 + xcd);
   if (rest >= n_rest) return;
@@ -328,7 +329,7 @@ __device__ __forceinline__ void mask_scores(f32x16& s0, f32x16& s1, int j0, int 
 // instead of competing for them ("ping-pong"), with a single barrier per tile.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(512, 1)
-fwd_bf16_pp_kernel(KArgs a, int T, int n_rest) {
+fwd_bf16_pp_kernel(KArgs a, int T, int il, int n_rest) {
   constexpr int BM = 256;
   constexpr int kStageBytes = 2 * kTileBytes;
   __shared__ __attribute__((aligned(1024))) char smem[3 * kStageBytes];   // [stage][K,V]
@@ -338,8 +339,9 @@ fwd_bf16_pp_kernel(KArgs a, int T, int n_rest) {
   const int grp = w >> 2;
 
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int y = uni(slot / T);
-  const int qt = T - 1 - (slot - y * T);
+  int y, rank;
+  decode_slot(slot, T, il, y, rank);
+  const int qt = T - 1 - rank;
   const int hr = uni(y % a.r);
   int rest = uni(uni(y / a.r) * 8 + xcd);
   if (rest >= n_rest) return;
@@ -488,17 +490,19 @@ int launch_fwd_bf16(const KArgs& a, hipStream_t st) {
   const int n_groups = a.B * a.Hkv * (a.N / a.G);
   if (a.G % 256 == 0 && !a.ragged) {
     const int T = a.G / 256;
-    const int blocks = 8 * T * a.r * ((n_groups + 7) / 8);
-    hipLaunchKernelGGL(fwd_bf16_pp_kernel, dim3(blocks), dim3(512), 0, st, a, T, n_groups);
+    const int il = interleave_for(T, 32);   // 32 CUs per XCD, one workgroup each
+    const int blocks = 8 * T * pad_to(a.r * ((n_groups + 7) / 8), il);
+    hipLaunchKernelGGL(fwd_bf16_pp_kernel, dim3(blocks), dim3(512), 0, st, a, T, il, n_groups);
     return hipGetLastError() == hipSuccess ? 0 : -1;
   }
   const int T = (a.G + 127) / 128;
   const int n_rest = a.B * a.Hkv * (a.N / a.G);
-  const int blocks = 8 * T * a.r * ((n_rest + 7) / 8);
+  const int il = interleave_for(T, 64);   // 32 CUs per XCD, two workgroups each
+  const int blocks = 8 * T * pad_to(a.r * ((n_rest + 7) / 8), il);
   if (a.ragged)
-    hipLaunchKernelGGL(fwd_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
+    hipLaunchKernelGGL(fwd_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, T, il, n_rest);
   else
-    hipLaunchKernelGGL(fwd_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, T, n_rest);
+    hipLaunchKernelGGL(fwd_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, T, il, n_rest);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -61,4 +61,18 @@ __device__ __forceinline__ int split_of_group(const KArgs& a, int g, int s) {
   return (s > 0 && g == a.N / a.G - 1) ? a.split : a.G;   // a.split == G means "no split"
 }
 
+// Block slot of one XCD -> (y, rank): y numbers the independent tile sequences of the launch
+// (one per batch, head, group ...), rank orders the T tiles of a sequence from heaviest (0)
+// to lightest.  `il` sequences are walked together, heaviest tiles of all of them first:
+// when a sequence has fewer tiles than the XCD has workgroup slots, several sequences are
+// resident anyway, and this order hands every slot about the same total work (a plain
+// sequence-by-sequence order leaves the slots that drew heavy tiles running at the end).
+__device__ __forceinline__ void decode_slot(int slot, int T, int il, int& y, int& rank) {
+  const int span = T * il;
+  const int chunk = __builtin_amdgcn_readfirstlane(slot / span);
+  const int within = slot - chunk * span;
+  rank = __builtin_amdgcn_readfirstlane(within / il);
+  y = chunk * il + (within - rank * il);
+}
+
 }  // namespace s2

@@ -21,4 +21,9 @@ int launch_delta(const KArgs& a, int dtype, hipStream_t st);
 // dk = partial[class 0] + partial[class 1] (same for dv), cast to the output type
 int launch_combine_partials(const KArgs& a, int dtype, hipStream_t st);
 
+// Number of tile sequences walked together (see decode_slot) for a kernel whose XCD holds
+// `slots` workgroups at a time, and the sequence count padded to a multiple of it.
+inline int interleave_for(int T, int slots) { return T >= slots ? 1 : (slots + T - 1) / T; }
+inline int pad_to(int n, int il) { return (n + il - 1) / il * il; }
+
 }  // namespace s2
