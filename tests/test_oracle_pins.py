@@ -307,3 +307,16 @@ def test_fp32_and_fp64_oracle_agree_on_a_long_group():
     b = orc.s2attn_fwd_bwd(q, k, v, do, G, shift=0, dtype=np.float64)
     for x, y in zip(a, b):
         assert np.abs(x - y).max() < 1e-4
+
+
+def test_fp32_and_fp64_oracle_agree_at_the_benchmark_group_size():
+    """One (kv head, group) slice at G = 8192, D = 128 (the size the GPU parity tests sample at
+    the benchmark configurations, where the oracle runs in fp32): fp32 and fp64 runs of the same
+    code agree to 1e-5, so the fp32 oracle's own rounding is far below the bf16 tolerance."""
+    G, D = 8192, 128
+    r = np.random.default_rng(31)
+    q, k, v, do = (r.standard_normal((1, G, 2, D)).astype(np.float32) for _ in range(4))
+    a = orc.s2attn_group_slice(q, k, v, do, G, 0, 0, 0, shift=0, dtype=np.float32)
+    b = orc.s2attn_group_slice(q, k, v, do, G, 0, 0, 0, shift=0, dtype=np.float64)
+    for name in ("o", "lse", "dq", "dk", "dv"):
+        assert np.abs(a[name] - b[name]).max() < 1e-5, name
