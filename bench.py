@@ -100,7 +100,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C3", help="C2 | C3 | C4 | C5 (bf16 configurations)")
+    ap.add_argument("--workload", default="C3",
+                    help="C2 | C3 | C4 | C5 (bf16 configurations); a '-full' suffix (e.g. C3-full) runs plain "
+                         "full causal attention of the same layer through the same kernels (G = N, no head "
+                         "shifts), for the S2-Attn : full attention time ratio")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this "
@@ -117,7 +120,11 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (there is no CPU fallback)", file=sys.stderr)
         sys.exit(2)
-    cfg = inputs.CONFIGS[args.workload]
+    full = args.workload.endswith("-full")
+    cfg = inputs.CONFIGS[args.workload[:-5] if full else args.workload]
+    if full:
+        cfg = inputs.S2Config(cfg.name + "-full", cfg.index, cfg.dtype, cfg.B, cfg.N, cfg.H, cfg.Hkv, cfg.D, cfg.N)
+    rule = binding.SHIFT_NONE if full else binding.SHIFT_SECOND_HALF
     if cfg.dtype != "bf16":
         raise SystemExit("bench workloads are the bf16 configurations")
     binding.lib()   # fail loudly before any work if the library is missing
@@ -133,14 +140,15 @@ def main():
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     ws = torch.empty(binding.bwd_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.Hkv, cfg.D, cfg.G), dtype=torch.uint8,
                      device="cuda")
-    p_bwd = binding.make_params(q, k, v, o, lse, cfg.G, dout=do, dq=dq, dk=dk, dv=dv, workspace=ws)
+    p_fwd = binding.make_params(q, k, v, o, lse, cfg.G, shift_rule=rule)
+    p_bwd = binding.make_params(q, k, v, o, lse, cfg.G, dout=do, dq=dq, dk=dk, dv=dv, workspace=ws, shift_rule=rule)
     stream = torch.cuda.current_stream().cuda_stream
     ev = HipEvents()
 
     def step(marks=None):
         if marks is not None:
             ev.record(marks[0], stream)
-        binding.s2attn_fwd(q, k, v, o, lse, cfg.G, stream=stream)
+        binding.s2attn_fwd_ex(p_fwd, stream=stream)
         if marks is not None:
             binding.s2attn_bwd_ex_marked(p_bwd, marks[1:5], stream=stream)
         else:
@@ -194,14 +202,16 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: S2-Attn layer fwd+bwd, B={cfg.B} N={cfg.N} H={cfg.H} Hkv={cfg.Hkv} "
-                               f"D={cfg.D} G={cfg.G} shift={cfg.G // 2} on heads >= H/2",
+                               f"D={cfg.D} G={cfg.G} " +
+                               ("no head shifts (full causal attention)" if full
+                                else f"shift={cfg.G // 2} on heads >= H/2"),
                    "effective_tflop_per_step": flops_total / 1e12},
         "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic},
         "kernels": kernels,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not full:   # one full-attention slice would be the whole N x N problem
         out["cpu_baseline"] = cpu_baseline(cfg, inp)
     print(json.dumps(out))
 
