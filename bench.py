@@ -181,6 +181,12 @@ def main():
             dur[n] += ev.elapsed_ms(m[j], m[j + 1])
     for n in names:
         dur[n] /= args.steps
+    # per-step device times from the same events: forward alone, backward alone (with the
+    # delta pre-pass) and both
+    per_step = {"fwd": [ev.elapsed_ms(m[0], m[1]) for m in marks],
+                "bwd": [ev.elapsed_ms(m[1], m[4]) for m in marks],
+                "fwd_bwd": [ev.elapsed_ms(m[0], m[4]) for m in marks]}
+    spread = {k_: {"median_ms": float(np.median(v_)), "min_ms": float(np.min(v_))} for k_, v_ in per_step.items()}
     for m in marks:
         for e in m:
             ev.destroy(e)
@@ -207,6 +213,7 @@ def main():
                                 else f"shift={cfg.G // 2} on heads >= H/2"),
                    "effective_tflop_per_step": flops_total / 1e12},
         "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS,
+        "device_time_per_step": spread,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic},
         "kernels": kernels,
