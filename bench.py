@@ -105,6 +105,9 @@ def main():
                          "full causal attention of the same layer through the same kernels (G = N, no head "
                          "shifts), for the S2-Attn : full attention time ratio")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--operands", choices=["normal", "zero"], default="normal",
+                    help="'zero' runs the same launches on all-zero q, k, v, dO: not the workload (the line says so "
+                         "in 'data'), a probe of how much of the time is the chip's data-dependent power limit")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known HBM traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -135,6 +138,9 @@ def main():
         return torch.from_numpy(inp[name + "_bits"].view(np.int16)).cuda().view(torch.bfloat16)
 
     q, k, v, do = dev("q"), dev("k"), dev("v"), dev("do")
+    if args.operands == "zero":
+        for t in (q, k, v, do):
+            t.zero_()
     o = torch.empty_like(q)
     lse = torch.empty((cfg.B, cfg.H, cfg.N), dtype=torch.float32, device="cuda")
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
@@ -206,7 +212,7 @@ def main():
         "metric": "S2-Attn fwd+bwd effective TFLOP/s (in-group causal FLOPs only)",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic" if args.operands == "normal" else "all-zero operands (power probe)",
         "config": {"workload": f"{cfg.name}: S2-Attn layer fwd+bwd, B={cfg.B} N={cfg.N} H={cfg.H} Hkv={cfg.Hkv} "
                                f"D={cfg.D} G={cfg.G} " +
                                ("no head shifts (full causal attention)" if full
@@ -218,7 +224,8 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic},
         "kernels": kernels,
     }
-    if not args.no_cpu_baseline and not full:   # one full-attention slice would be the whole N x N problem
+    # (one full-attention slice would be the whole N x N problem; the zero probe is not the workload)
+    if not args.no_cpu_baseline and not full and args.operands == "normal":
         out["cpu_baseline"] = cpu_baseline(cfg, inp)
     print(json.dumps(out))
 
