@@ -19,9 +19,15 @@
  *   - Grouped-query attention: query head h reads kv head h / (H/Hkv); whether a
  *     head is shifted is a property of the query head; dk, dv sum over the query
  *     heads that share a kv head.
- *   - Return value: 0 (S2ATTN_OK) or a negative S2ATTN_ERR_* code.  On error
- *     nothing has been launched.  The library has no mutable global state;
- *     calls are re-entrant and may be issued from several host threads.
+ *   - Return value: 0 (S2ATTN_OK) or a negative S2ATTN_ERR_* code.  Argument errors
+ *     are found before anything is launched.  S2ATTN_ERR_LAUNCH means HIP refused a
+ *     kernel launch: the backward enqueues several kernels, so earlier ones of the
+ *     same call may already be on the stream and the outputs are then undefined.
+ *     The library has no mutable global state; calls are re-entrant and may be
+ *     issued from several host threads.
+ *   - bf16 calls take any even G and any shift; G a multiple of 128 with the shift
+ *     (and, under Variant 2, G - shift) a multiple of 64 (128) runs the faster
+ *     tile-aligned kernels.
  *   - Tensor pointers must be 16-byte aligned.
  */
 #ifndef S2ATTN_H
@@ -47,9 +53,7 @@ enum {
   S2ATTN_ERR_GROUP = -4,       /* N % G != 0, or G odd, or shift outside [0, G) */
   S2ATTN_ERR_HEADS = -5,       /* H odd (half of the heads shift), H % Hkv != 0, or inconsistent head sharding */
   S2ATTN_ERR_HEADDIM = -6,     /* D not supported: fp32 needs D in {64,128}; bf16 needs D == 128 */
-  S2ATTN_ERR_TILE = -7,        /* bf16 path with S2ATTN_WRAP_SPLIT: G must be a multiple of 128 and shift of 64
-                                  (S2ATTN_WRAP_JOINT takes any even G and any shift; multiples of 128 / 64
-                                  run the fast aligned path) */
+  /* -7 is unused (it was a tile-alignment error that no longer exists) */
   S2ATTN_ERR_WORKSPACE = -8,   /* backward workspace missing or too small */
   S2ATTN_ERR_DTYPE = -9,       /* unknown dtype / rule / variant value */
   S2ATTN_ERR_DEVICE = -10,     /* current device is not gfx950 */

@@ -64,6 +64,23 @@ bool strides_ok(const long long (&st)[3], int B, int heads, int D, int align) {
   return true;
 }
 
+// Output tensors must not alias themselves: ordering the three strided axes by stride, each
+// stride has to cover the whole extent of the axes below it (the head-dim axis, D contiguous
+// elements, is the innermost).
+bool rows_disjoint(const long long (&st)[3], int B, int N, int heads, int D) {
+  if (st[0] == 0 && st[1] == 0 && st[2] == 0) return true;
+  struct Axis { long long stride; long long extent; };
+  Axis ax[3] = {{st[0], B}, {st[1], N}, {st[2], heads}};
+  std::sort(ax, ax + 3, [](const Axis& x, const Axis& y) { return x.stride < y.stride; });
+  long long span = D;   // elements covered by everything below the current axis
+  for (const Axis& x : ax) {
+    if (x.extent <= 1) continue;
+    if (x.stride < span) return false;
+    span = x.stride * (x.extent - 1) + span;
+  }
+  return true;
+}
+
 int check_common(const s2attn_params* p, int backward) {
   if (!p) return S2ATTN_ERR_NULL;
   if (p->dtype != S2ATTN_BF16 && p->dtype != S2ATTN_F32) return S2ATTN_ERR_DTYPE;
@@ -85,10 +102,6 @@ int check_common(const s2attn_params* p, int backward) {
     if (p->D != 64 && p->D != 128) return S2ATTN_ERR_HEADDIM;
   } else {
     if (p->D != 128) return S2ATTN_ERR_HEADDIM;
-    // Variant 2 moves the first visible key of a tile row block; the bf16 kernels only
-    // do that at tile boundaries
-    if (p->wrap_variant == S2ATTN_WRAP_SPLIT && shift > 0 && (p->G % 128 != 0 || shift % 64 != 0))
-      return S2ATTN_ERR_TILE;
   }
   // grid z carries batch * heads (* 2 classes); element offsets are 64-bit
   if ((long long)p->B * p->H * 2 > 65535 || (long long)p->N / p->G > 65535) return S2ATTN_ERR_TOO_LARGE;
@@ -101,6 +114,10 @@ int check_common(const s2attn_params* p, int backward) {
   if (backward && (!strides_ok(p->dq_strides, p->B, p->H, p->D, align) ||
                    !strides_ok(p->dk_strides, p->B, p->Hkv, p->D, align) ||
                    !strides_ok(p->dv_strides, p->B, p->Hkv, p->D, align)))
+    return S2ATTN_ERR_STRIDE;
+  if (backward && (!rows_disjoint(p->dq_strides, p->B, p->N, p->H, p->D) ||
+                   !rows_disjoint(p->dk_strides, p->B, p->N, p->Hkv, p->D) ||
+                   !rows_disjoint(p->dv_strides, p->B, p->N, p->Hkv, p->D)))
     return S2ATTN_ERR_STRIDE;
   const void* need_fwd[] = {p->q, p->k, p->v, p->o, p->lse};
   for (const void* x : need_fwd) {
@@ -167,7 +184,8 @@ s2::KArgs make_kargs(const s2attn_params* p) {
   a.shifted_from = shifted_from(p, a.shift);
   a.split = (p->wrap_variant == S2ATTN_WRAP_SPLIT && a.shift > 0) ? p->G - a.shift : p->G;
   a.mixed = kv_heads_mixed(p->H, p->Hkv, a.shifted_from) ? 1 : 0;
-  a.ragged = (p->dtype == S2ATTN_BF16 && (p->G % 128 != 0 || a.shift % 64 != 0)) ? 1 : 0;
+  a.ragged = (p->dtype == S2ATTN_BF16 &&
+              (p->G % 128 != 0 || a.shift % 64 != 0 || (a.split < p->G && a.split % 128 != 0))) ? 1 : 0;
   a.scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->D);
   a.scale_log2 = a.scale * 1.4426950408889634f;
   return a;
@@ -295,7 +313,6 @@ const char* s2attn_strerror(int code) {
     case S2ATTN_ERR_GROUP: return "need N % G == 0, G even and 0 <= shift < G";
     case S2ATTN_ERR_HEADS: return "need H even and H % Hkv == 0";
     case S2ATTN_ERR_HEADDIM: return "unsupported head dimension (fp32: 64 or 128; bf16: 128)";
-    case S2ATTN_ERR_TILE: return "bf16 path with the split wrap-around group needs G to be a multiple of 128 and shift a multiple of 64";
     case S2ATTN_ERR_WORKSPACE: return "backward workspace missing or smaller than s2attn_bwd_workspace_bytes";
     case S2ATTN_ERR_DTYPE: return "unknown dtype, shift rule or wrap variant";
     case S2ATTN_ERR_DEVICE: return "current device is not gfx950 (MI355X)";

@@ -221,12 +221,21 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
   h_lo = uni(h_lo);
 
   const int s = uni(cls ? a.shift : 0);
-  const int split = uni(split_of_group(a, gidx, s));
+  // the causal run this block works in (see the forward kernel): the aligned kernel cuts the
+  // query range of a split wrap-around group at `split`, a multiple of the tile; the ragged
+  // one runs the two blocks as runs of their own
+  Run run{gidx * a.G, a.G};
+  int split = uni(split_of_group(a, gidx, s));
+  if constexpr (RAGGED) {
+    if (!run_of_tile(a, gidx, s, kQTileRows, jt, run)) return;
+    run.p0 = uni(run.p0); run.len = uni(run.len);
+    split = run.len;
+  }
   const int j0 = jt * 128;
   const int kw0 = j0 + 32 * w;                       // first key of this wave
   const int key = kw0 + l32;
   // query rows visible to this workgroup's keys: [j0, q_end)
-  const int q_end = uni((j0 + 127 < split) ? split : a.G);
+  const int q_end = uni((j0 < split) ? split : run.len);
   const int it_begin = uni(j0 / kQTileRows);
   const int nq = uni((q_end - j0 + kQTileRows - 1) / kQTileRows);
   const int n_iter = nheads * nq;
@@ -238,7 +247,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
   // K^T and -V^T fragments of this wave's 32 keys (the sign: see init_dp)
   bf16x8 kf[8], vf[8];
   {
-    const int tok = row_token(a, gidx, key, s);
+    const int tok = run_token(a, run, key, s);
     const bf16x8* ksrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.k) + row_off(a.sk, b, tok, c));
     const bf16x8* vsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.v) + row_off(a.sv, b, tok, c));
 #pragma unroll
@@ -264,7 +273,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
       if constexpr (!RAGGED) {
-        const uint32_t tok0 = (uint32_t)token_of(gidx * a.G + q0 + 64 * hf, s, a.N);
+        const uint32_t tok0 = (uint32_t)token_of(run.p0 + q0 + 64 * hf, s, a.N);
         const uint64_t qb = q_batch + tok0 * q_row_bytes + (uint64_t)h * a.sq.h * 2;
         const uint64_t dob = do_batch + tok0 * do_row_bytes + (uint64_t)h * a.so.h * 2;
 #pragma unroll
@@ -280,13 +289,13 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
       } else {   // every row finds its own token; padding rows repeat the last row of the group
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-          const int tok = row_token(a, gidx, q0 + 64 * hf + 16 * p + st_row, s);
+          const int tok = run_token(a, run, q0 + 64 * hf + 16 * p + st_row, s);
           dma16(qp + row_off(a.sq, b, tok, h) * 2 + st_chunk, qs + (64 * hf + 16 * p) * kRowBytes);
           dma16(dop + row_off(a.so, b, tok, h) * 2 + st_chunk,
                 qs + (64 * hf + 16 * p) * kRowBytes + kQTileBytes);
         }
         if (w == hf) {
-          const size_t ro = ((size_t)b * a.H + h) * a.N + row_token(a, gidx, q0 + 64 * hf + lane, s);
+          const size_t ro = ((size_t)b * a.H + h) * a.N + run_token(a, run, q0 + 64 * hf + lane, s);
           dma4(a.lse2 + ro, rows_base + ((stage * 2 + 0) * kQTileRows + 64 * hf) * 4);
           dma4(a.delta + ro, rows_base + ((stage * 2 + 1) * kQTileRows + 64 * hf) * 4);
         }
@@ -323,7 +332,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
   // Per head: the diagonal tile first, then the interior tiles in a loop of their own (the
   // hot loop holds nothing but the pipelined interior tile), then, for a group size that is
   // not a multiple of the tile, the partial last tile.
-  const bool has_tail = RAGGED && (a.G % kQTileRows != 0);
+  const bool has_tail = RAGGED && (run.len % kQTileRows != 0);
   const int n_full = has_tail ? nq - 1 : nq;           // tiles [0, n_full) are complete
   if (n_iter > 0) issue_tile(0, 0, 0);
   int n = 0;
@@ -333,7 +342,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
       if constexpr (RAGGED) {
         // query rows >= G (padding of a partial tile) give P = 0; blocks before this wave's
         // keys are skipped
-        for (int mb = w; mb < 4; ++mb) dkdv_block<true>(t, mb, j0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, a.G);
+        for (int mb = w; mb < 4; ++mb) dkdv_block<true>(t, mb, j0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, run.len);
       } else {
         // block mb < w is entirely before this wave's keys, block w is masked
         dkdv_block<true>(t, w, j0 + 32 * w, key, kf, vf, dk_acc, dv_acc);
@@ -343,14 +352,12 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
     }
     for (int it = 1; it < n_full; ++it, ++n) {
       const DkdvTile t = begin_tile(n, hh, it);
-      // Variant 2: keys of the first block see no query of the second block
-      if (kw0 + 31 < split && j0 + it * kQTileRows >= split) continue;
       dkdv_interior_tile(t, kf, vf, dk_acc, dv_acc);
     }
     if (has_tail && nq > 1) {
       const DkdvTile t = begin_tile(n, hh, nq - 1);
       const int q0 = j0 + (nq - 1) * kQTileRows;
-      for (int mb = 0; mb < 4; ++mb) dkdv_block<true>(t, mb, q0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, a.G);
+      for (int mb = 0; mb < 4; ++mb) dkdv_block<true>(t, mb, q0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, run.len);
       ++n;
     }
   }
@@ -362,8 +369,8 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
     const size_t kv_elems = (size_t)a.B * a.N * a.Hkv * 128;
     float* dk_out = a.dkv_partial + (size_t)cls * kv_elems;
     float* dv_out = a.dkv_partial + (size_t)(2 + cls) * kv_elems;
-    if (key >= a.G) return;   // padding key of a partial tile
-    const int tok = token_of(gidx * a.G + key, s, a.N);
+    if (key >= run.len) return;   // padding key of a partial tile
+    const int tok = token_of(run.p0 + key, s, a.N);
     const size_t base = ((size_t)((size_t)b * a.N + tok) * a.Hkv + c) * 128;   // partials are contiguous
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -388,8 +395,8 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
-    if (kw0 + row >= a.G) continue;   // padding key of a partial tile
-    const int tok = token_of(gidx * a.G + kw0 + row, s, a.N);
+    if (kw0 + row >= run.len) continue;   // padding key of a partial tile
+    const int tok = token_of(run.p0 + kw0 + row, s, a.N);
     *reinterpret_cast<uint4*>(dkp + row_off(a.sdk, b, tok, c) + ch * 8) =
         *reinterpret_cast<const uint4*>(rk + tile_off(row, ch));
     *reinterpret_cast<uint4*>(dvp + row_off(a.sdv, b, tok, c) + ch * 8) =
@@ -498,7 +505,7 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   int y, rank;
   decode_slot(slot, T, il, y, rank);
-  const int qt = T - 1 - rank;
+  int qt = T - 1 - rank;
   const int hr = uni(y % a.r);
   int rest = uni(uni(y / a.r) * 8 + xcd);
   if (rest >= n_rest) return;
@@ -509,7 +516,13 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   const int h = c * a.r + hr;
 
   const int s = uni(shift_of_head(a, h));
-  const int split = uni(split_of_group(a, gidx, s));
+  Run run{gidx * a.G, a.G};                        // the causal run of this block (see the forward kernel)
+  int split = uni(split_of_group(a, gidx, s));
+  if constexpr (RAGGED) {
+    if (!run_of_tile(a, gidx, s, BM, qt, run)) return;
+    run.p0 = uni(run.p0); run.len = uni(run.len);
+    split = run.len;
+  }
   const int i0 = qt * BM;
   const int qw0 = i0 + w * 32;
   const int qrow = qw0 + l32;
@@ -524,7 +537,7 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   bf16x8 qf[8], dof[8];
   float lse2, delta;
   {
-    const int tok = row_token(a, gidx, qrow, s);
+    const int tok = run_token(a, run, qrow, s);
     const bf16x8* qsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.q) + row_off(a.sq, b, tok, h));
     const bf16x8* dsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.dout) + row_off(a.so, b, tok, h));
 #pragma unroll
@@ -546,7 +559,7 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   auto issue_tile = [&](int jt, int stage) {
     const uint32_t ks = smem_base + stage * 2 * kTileBytes + 4 * w * kRowBytes;
     if constexpr (!RAGGED) {
-      const uint32_t tok0 = (uint32_t)token_of(gidx * a.G + jt * BN, s, a.N);   // an aligned tile never straddles the wrap
+      const uint32_t tok0 = (uint32_t)token_of(run.p0 + jt * BN, s, a.N);   // an aligned tile never straddles the wrap
       const uint64_t kb = k_head + tok0 * k_row_bytes, vb = v_head + tok0 * v_row_bytes;
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
@@ -556,7 +569,7 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
     } else {   // every row finds its own token; padding rows repeat the last row of the group
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
-        const int tok = row_token(a, gidx, jt * BN + 16 * p + st_row, s);
+        const int tok = run_token(a, run, jt * BN + 16 * p + st_row, s);
         dma16(kp + row_off(a.sk, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes);
         dma16(vp + row_off(a.sv, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes + kTileBytes);
       }
@@ -598,8 +611,8 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
-    if (qw0 + row >= a.G) continue;   // padding row of a partial tile
-    const int tok = token_of(gidx * a.G + qw0 + row, s, a.N);
+    if (qw0 + row >= run.len) continue;   // padding row of a partial tile
+    const int tok = token_of(run.p0 + qw0 + row, s, a.N);
     *reinterpret_cast<uint4*>(dqp + row_off(a.sdq, b, tok, h) + ch * 8) =
         *reinterpret_cast<const uint4*>(region + tile_off(row, ch));
   }
@@ -608,12 +621,10 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
 }  // namespace
 
 int launch_bwd_dkdv_bf16(const KArgs& a, hipStream_t st) {
-#ifndef S2X_NO_SPLIT
   if (dkdv_split_applies(a)) return launch_bwd_dkdv_split_bf16(a, st);
-#endif
   const int NG = a.N / a.G;
   const int ncls = a.mixed ? 2 : 1;
-  const int T = (a.G + 127) / 128;
+  const int T = a.ragged ? ragged_tiles(a, 128) : a.G / 128;
   const int n_rest = a.B * a.Hkv * ncls * NG;
   const int il = interleave_for(T, 32);   // 32 CUs per XCD, one workgroup each
   const int blocks = 8 * T * pad_to((n_rest + 7) / 8, il);
@@ -626,7 +637,7 @@ int launch_bwd_dkdv_bf16(const KArgs& a, hipStream_t st) {
 
 int launch_bwd_dq_bf16(const KArgs& a, hipStream_t st) {
   const int NG = a.N / a.G;
-  const int T = (a.G + 127) / 128;
+  const int T = a.ragged ? ragged_tiles(a, 128) : a.G / 128;
   const int n_rest = a.B * a.Hkv * NG;
   const int il = interleave_for(T, 64);   // 32 CUs per XCD, two workgroups each
   const int blocks = 8 * T * pad_to(a.r * ((n_rest + 7) / 8), il);

@@ -1,7 +1,7 @@
 // bf16 S2-Attn backward, dK/dV kernel for gfx950, two waves per SIMD ("role split").
-// Used for tile-aligned shapes (G % 128 == 0, shift % 64 == 0) without Variant 2 and with
-// every kv head wholly shifted or unshifted; everything else runs the one-wave-per-SIMD
-// kernel of s2attn_bf16_bwd.hip, which computes the same thing.
+// Used for tile-aligned shapes (G % 128 == 0, shift % 64 == 0, a Variant 2 split that is a
+// multiple of 128) with every kv head wholly shifted or unshifted; everything else runs the
+// one-wave-per-SIMD kernel of s2attn_bf16_bwd.hip, which computes the same thing.
 //
 // A workgroup (8 waves on one CU) owns 128 keys of one (batch, kv head, group) in the rolled
 // frame of the kv head's class (LongLoRA Algorithm 1: the shift is row addressing only) and
@@ -120,7 +120,10 @@ bwd_dkdv_split_kernel(KArgs a, int T, int il, int n_rest) {
   const int j0 = jt * 128;
   const int kw0 = j0 + 32 * kb;                      // first key of this wave
   const int key = kw0 + l32;
-  const int nq = uni((a.G - j0) / kQT);              // query tiles [j0, G) of one head, >= 2
+  // query rows visible to these keys: [j0, G), or [j0, split) for the first block of a split
+  // wrap-around group (Variant 2, Appendix B.3; the split is a multiple of the key tile here)
+  const int split = uni(split_of_group(a, gidx, s));
+  const int nq = uni(((j0 < split ? split : a.G) - j0) / kQT);   // query tiles of one head, >= 2
   const int n_iter = a.r * nq;
   const float c2 = a.scale_log2;
 
@@ -322,7 +325,7 @@ bwd_dkdv_split_kernel(KArgs a, int T, int il, int n_rest) {
 }  // namespace
 
 bool dkdv_split_applies(const KArgs& a) {
-  return !a.ragged && !a.mixed && a.split == a.G;
+  return !a.ragged && !a.mixed;
 }
 
 int launch_bwd_dkdv_split_bf16(const KArgs& a, hipStream_t st) {

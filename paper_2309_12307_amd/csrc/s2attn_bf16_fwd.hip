@@ -135,7 +135,7 @@ __device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], co
 // Normalises a wave's 32 x 128 output block, transposes it through the wave's private
 // 8 KB LDS region and stores it (and lse) at the un-rolled token rows.  Contains one
 // workgroup barrier between the LDS writes and reads.
-__device__ __forceinline__ void fwd_epilogue(const KArgs& a, FwdState& st, char* Os, int b, int h, int gidx, int s,
+__device__ __forceinline__ void fwd_epilogue(const KArgs& a, FwdState& st, char* Os, int b, int h, const Run& run, int s,
                                              int qw0, float c2, int lane, int l32, int g32) {
   __bf16* op = static_cast<__bf16*>(a.o);
   const float l_tot = sum_halves(st.l_run);
@@ -153,19 +153,21 @@ __device__ __forceinline__ void fwd_epilogue(const KArgs& a, FwdState& st, char*
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
     const uint4 val = *reinterpret_cast<const uint4*>(Os + tile_off(row, ch));
-    if (qw0 + row < a.G) {   // rows past the group end are padding of a partial tile
-      const int tok = token_of(gidx * a.G + qw0 + row, s, a.N);
+    if (qw0 + row < run.len) {   // rows past the end of the run are padding of a partial tile
+      const int tok = token_of(run.p0 + qw0 + row, s, a.N);
       *reinterpret_cast<uint4*>(op + row_off(a.so, b, tok, h) + ch * 8) = val;
     }
   }
-  if (g32 == 0 && qw0 + l32 < a.G) {
-    const int tok = token_of(gidx * a.G + qw0 + l32, s, a.N);
+  if (g32 == 0 && qw0 + l32 < run.len) {
+    const int tok = token_of(run.p0 + qw0 + l32, s, a.N);
     a.lse[((size_t)b * a.H + h) * a.N + tok] = (st.m_run * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
   }
 }
 
-// RAGGED: G is not a multiple of 128 or the shift not of 64 -- tiles may be partial and
-// the wrap point may fall inside one, so every staged row finds its own token.
+// RAGGED: G is not a multiple of 128, the shift not of 64 or a Variant 2 split not of 128 --
+// tiles may be partial and the wrap point may fall inside one, so every staged row finds
+// its own token, and the two halves of a split wrap-around group run as causal runs of
+// their own (run_of_tile).
 template <bool RAGGED>
 __global__ void __launch_bounds__(256, 2)
 fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
@@ -183,7 +185,7 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   int y, rank;
   decode_slot(slot, T, il, y, rank);
-  const int qt = T - 1 - rank;
+  int qt = T - 1 - rank;
   const int hr = uni(y % a.r);
   int rest = uni(uni(y / a.r) * 8 + xcd);
   if (rest >= n_rest) return;
@@ -194,7 +196,16 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   const int h = c * a.r + hr;
 
   const int s = uni(shift_of_head(a, h));
-  const int split = uni(split_of_group(a, gidx, s));
+  // the causal run this block works in and the first row of the other block of a split
+  // wrap-around group inside it (aligned kernels skip whole tiles at `split`; the ragged
+  // ones run the two blocks as runs of their own and see no split)
+  Run run{gidx * a.G, a.G};
+  int split = uni(split_of_group(a, gidx, s));
+  if constexpr (RAGGED) {
+    if (!run_of_tile(a, gidx, s, BM, qt, run)) return;
+    run.p0 = uni(run.p0); run.len = uni(run.len);
+    split = run.len;
+  }
   const int i0 = qt * BM;
   const int qw0 = i0 + w * 32;                      // first query row of this wave
   const int qrow = qw0 + l32;
@@ -210,7 +221,7 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   // ---- Q^T fragments of this wave, straight from global memory
   bf16x8 qf[8];
   {
-    const int tok = row_token(a, gidx, qrow, s);
+    const int tok = run_token(a, run, qrow, s);
     const bf16x8* src = reinterpret_cast<const bf16x8*>(qp + row_off(a.sq, b, tok, h));
 #pragma unroll
     for (int st = 0; st < 8; ++st) qf[st] = src[2 * st + g32];
@@ -231,7 +242,7 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   auto issue_tile = [&](int jt, int stage) {
     const uint32_t ks = smem_base + stage * 2 * kTileBytes + 4 * w * kRowBytes;
     if constexpr (!RAGGED) {
-      const uint32_t tok0 = (uint32_t)token_of(gidx * a.G + jt * BN, s, a.N);   // an aligned tile never straddles the wrap
+      const uint32_t tok0 = (uint32_t)token_of(run.p0 + jt * BN, s, a.N);   // an aligned tile never straddles the wrap
       const uint64_t kb = k_head + tok0 * k_row_bytes, vb = v_head + tok0 * v_row_bytes;
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
@@ -241,7 +252,7 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
     } else {   // every row finds its own token; padding rows repeat the last row of the group
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
-        const int tok = row_token(a, gidx, jt * BN + 16 * p + st_row, s);
+        const int tok = run_token(a, run, jt * BN + 16 * p + st_row, s);
         dma16(kp + row_off(a.sk, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes);
         dma16(vp + row_off(a.sv, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes + kTileBytes);
       }
@@ -275,7 +286,7 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   __syncthreads();
 
   // ---- epilogue: normalise, transpose through LDS, store at un-rolled token rows
-  fwd_epilogue(a, st, smem + w * (32 * kRowBytes), b, h, gidx, s, qw0, c2, lane, l32, g32);
+  fwd_epilogue(a, st, smem + w * (32 * kRowBytes), b, h, run, s, qw0, c2, lane, l32, g32);
 }
 
 // ---- the matrix block of the eight-wave kernel as 8 steps of 4 MFMAs, each fed by 4
@@ -481,7 +492,7 @@ fwd_bf16_pp_kernel(KArgs a, int T, int il, int n_rest) {
     const int t = st_cur; st_cur = st_nxt; st_nxt = st_free; st_free = t;
   }
   __syncthreads();
-  fwd_epilogue(a, st, smem + w * (32 * kRowBytes), b, h, gidx, s, qw0, c2, lane, l32, g32);
+  fwd_epilogue(a, st, smem + w * (32 * kRowBytes), b, h, Run{gidx * a.G, a.G}, s, qw0, c2, lane, l32, g32);
 }
 
 }  // namespace
@@ -495,7 +506,7 @@ int launch_fwd_bf16(const KArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(fwd_bf16_pp_kernel, dim3(blocks), dim3(512), 0, st, a, T, il, n_groups);
     return hipGetLastError() == hipSuccess ? 0 : -1;
   }
-  const int T = (a.G + 127) / 128;
+  const int T = a.ragged ? ragged_tiles(a, 128) : a.G / 128;
   const int n_rest = a.B * a.Hkv * (a.N / a.G);
   const int il = interleave_for(T, 64);   // 32 CUs per XCD, two workgroups each
   const int blocks = 8 * T * pad_to(a.r * ((n_rest + 7) / 8), il);

@@ -27,8 +27,8 @@ struct KArgs {
   int shifted_from;                          // heads >= shifted_from use the shifted partition
   int split;                                 // Variant 2: rows [0,split) | [split,G) of the wrap group; G = off
   int mixed;                                 // some kv head serves both head classes
-  int ragged;                                // bf16 path: G % 128 != 0 or shift % 64 != 0 (partial tiles,
-                                             // wrap point inside a tile)
+  int ragged;                                // bf16 path: G % 128 != 0, shift % 64 != 0 or a Variant 2 split that
+                                             // is not a multiple of 128 (partial tiles, wrap point inside a tile)
   float scale;                               // softmax scale
   float scale_log2;                          // scale * log2(e)
 };
@@ -45,10 +45,18 @@ __device__ __forceinline__ size_t row_off(const TStride& s, int b, int t, int h)
   return (size_t)((long long)b * s.b + (long long)t * s.t + (long long)h * s.h);
 }
 
-// Token of in-group row i of group g, with rows past the end of the group (padding of a
-// partial tile) clamped to the last row so that every load stays inside the tensor.
-__device__ __forceinline__ int row_token(const KArgs& a, int g, int i, int s) {
-  return token_of(g * a.G + min(i, a.G - 1), s, a.N);
+// A causal run: `len` consecutive rolled positions starting at `p0` inside which row i
+// sees rows 0 .. i.  Normally a whole group (p0 = g * G, len = G); under Variant 2
+// (Appendix B.3) the wrap-around group of a shifted head is two runs, [0, split) and
+// [split, G) of the group.
+struct Run {
+  int p0, len;
+};
+
+// Token of row i of a run, with rows past its end (padding of a partial tile) clamped to
+// the last row so that every load stays inside the tensor.
+__device__ __forceinline__ int run_token(const KArgs& a, const Run& run, int i, int s) {
+  return token_of(run.p0 + min(i, run.len - 1), s, a.N);
 }
 
 __device__ __forceinline__ int shift_of_head(const KArgs& a, int h) {
@@ -73,6 +81,35 @@ __device__ __forceinline__ void decode_slot(int slot, int T, int il, int& y, int
   const int within = slot - chunk * span;
   rank = __builtin_amdgcn_readfirstlane(within / il);
   y = chunk * il + (within - rank * il);
+}
+
+// Kernels built for partial tiles treat Variant 2 by running the two halves of the
+// wrap-around group as causal runs of their own: tile index `t` of the group (tiles of
+// `tile` rows, first run's tiles first) -> the run and the tile index inside it.  Returns
+// false when the group has no such tile (the grid is sized for the worst case).
+__device__ __forceinline__ bool run_of_tile(const KArgs& a, int g, int s, int tile, int& t, Run& run) {
+  run.p0 = g * a.G;
+  run.len = a.G;
+  const int split = split_of_group(a, g, s);
+  if (split < a.G) {
+    const int t_first = (split + tile - 1) / tile;
+    if (t < t_first) {
+      run.len = split;
+    } else {
+      t -= t_first;
+      run.p0 += split;
+      run.len = a.G - split;
+    }
+  }
+  return t * tile < run.len;
+}
+
+// Tiles of `tile` rows that a group needs at most under run_of_tile.
+inline int ragged_tiles(const KArgs& a, int tile) {
+  const int whole = (a.G + tile - 1) / tile;
+  if (a.split >= a.G) return whole;
+  const int two = (a.split + tile - 1) / tile + (a.G - a.split + tile - 1) / tile;
+  return two > whole ? two : whole;
 }
 
 }  // namespace s2

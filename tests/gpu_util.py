@@ -53,6 +53,37 @@ def run_hip(inp: dict, G: int, dtype: str, backward=True, **ex):
     return out
 
 
+TOL_BF16 = 2e-2      # stated bound on o, dq, dk, dv in bf16 mode, against the fp32 oracle
+TOL_LSE = 2e-3
+
+
+def half_ulp_bf16(ref):
+    """Half the spacing of bf16 numbers at |ref|: what rounding the exact value to the bf16
+    output costs at most (2^-9 |ref| .. 2^-8 |ref|)."""
+    _, ex = np.frexp(np.abs(np.asarray(ref, dtype=np.float32)))     # |ref| = m * 2^ex, m in [0.5, 1)
+    return np.ldexp(np.float32(1.0), ex - 9).astype(np.float64)
+
+
+def bf16_tol(ref):
+    """Per-element bound for a bf16 output tensor: the stated 2e-2 on the value the kernel
+    holds in fp32, plus the rounding of that value to the bf16 it has to be stored as.
+    No allowance for the number of heads or terms summed."""
+    return TOL_BF16 + half_ulp_bf16(ref)
+
+
+def check_bf16_tensor(name, got, ref):
+    """Asserts |got - ref| <= bf16_tol(ref) element-wise; returns (max error, max error beyond
+    the output rounding)."""
+    assert np.all(np.isfinite(got)), name
+    err = np.abs(got.astype(np.float64) - ref)
+    tol = bf16_tol(ref)
+    if (err > tol).any():
+        idx = np.unravel_index(np.argmax(err - tol), err.shape)
+        raise AssertionError(f"{name}: {(err > tol).sum()} elements over tolerance; worst at {idx}: "
+                             f"got {got[idx]}, ref {ref[idx]}, err {err[idx]}, tol {tol[idx]}")
+    return float(err.max()), float((err - half_ulp_bf16(ref)).max())
+
+
 def max_abs(a, b):
     return float(np.max(np.abs(np.asarray(a, dtype=np.float64) - np.asarray(b, dtype=np.float64))))
 

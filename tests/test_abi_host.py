@@ -27,8 +27,9 @@ def test_library_exports_every_declared_symbol():
 
 def test_strerror_and_flops():
     assert binding.strerror(0) == "ok"
-    for code in range(-12, 0):
-        assert "error code" not in binding.strerror(code)
+    for code in range(-13, 0):
+        if code != -7:        # -7 is unused
+            assert "error code" not in binding.strerror(code)
     assert "error code" in binding.strerror(-99)
     # C3 of the benchmark: 7.698 effective TFLOP forward+backward
     assert abs(binding.effective_flops(1, 32768, 32, 128, 8192, 2) / 1e12 - 7.698) < 1e-3
@@ -79,8 +80,6 @@ def test_validator_accepts_benchmark_shapes():
     (dict(H=4, Hkv=3), -5),
     (dict(D=96), -6),
     (dict(D=64), -6),                         # bf16 supports D = 128 only
-    (dict(G=200, N=1000, wrap_variant=2), -7),  # Variant 2 needs tile-aligned G and shift in bf16
-    (dict(shift=100, wrap_variant=2), -7),
     (dict(workspace_bytes=16), -8),
     (dict(workspace=0), -8),
     (dict(dtype=5), -9),
@@ -90,6 +89,8 @@ def test_validator_accepts_benchmark_shapes():
     (dict(q_strides=(1024 * 4 * 128 * 3, 3 * 4 * 128, 100)), -13),    # head stride not a multiple of 8
     (dict(k_strides=(1024 * 4 * 128, -512, 128)), -13),               # negative
     (dict(dv_strides=(1024 * 4 * 128, 512, 64)), -13),                # heads would overlap
+    (dict(dq_strides=(1024 * 4 * 128, 256, 128)), -13),               # tokens would overlap the 4 heads of a token
+    (dict(dk_strides=(1024 * 128, 128, 1024 * 128), B=2), -13),       # batches would overlap the heads
     (dict(k_strides=((1 << 26) * 1024, 1 << 26, 128)), -13),          # token stride beyond the kernels' 32-bit row offsets
 ])
 def test_validator_codes(kw, code):
@@ -102,6 +103,11 @@ def test_validator_codes(kw, code):
     dict(G=25000, N=100000),            # the paper's 100k-token setting (Section 4.2), G = N / 4
     dict(shift=2),
     dict(wrap_variant=2),               # aligned Variant 2
+    dict(G=200, N=1000, wrap_variant=2),  # Variant 2 with a partial last tile
+    dict(shift=100, wrap_variant=2),      # Variant 2 split inside a tile
+    dict(G=384, N=1536, wrap_variant=2),  # split at 192: a multiple of 64 but not of the 128-key tile
+    dict(dq_strides=(4 * 1024 * 128, 128, 1024 * 128), dk_strides=(4 * 1024 * 128, 128, 1024 * 128),
+         dv_strides=(4 * 1024 * 128, 128, 1024 * 128)),   # head-major (B, H, N, D) gradients: rows stay disjoint
 ])
 def test_validator_accepts_unaligned_groups_in_bf16(kw):
     assert binding.check_args(params(**kw), True) == 0

@@ -93,14 +93,14 @@ def test_peaked_softmax_rows(case):
     if dtype == "f32":
         compare(dtype, out, ref)
         return
-    # bf16: the absolute 2e-2 as everywhere; the relative term, which takes over above |ref| = 2.5,
-    # is 8e-3 here instead of 5e-3: 2^-8 for the rounding of the output as before, and 2^-8 instead of
-    # 1.1e-3 for the rounding of P, whose entries near 1 each err by up to 2^-9 with nothing to average
-    # over when one query dominates a key's column
+    # bf16: the usual bound (2e-2 plus the rounding of the stored output) plus 2^-8 |ref| for the
+    # bf16 rounding of the P and dS operands: entries of P near 1 each err by up to 2^-9, and so
+    # do the matching dS entries, with nothing to average over when one query dominates a key's
+    # column (on N(0,1) operands thousands of small entries share a column and this term vanishes)
+    from gpu_util import bf16_tol
     o, lse, dq, dk, dv = ref
     assert np.abs(out["lse"] - lse).max() <= 2e-3
-    heads = o.shape[2] // dk.shape[2]
-    for name, r, hs in (("o", o, 1), ("dq", dq, 1), ("dk", dk, heads), ("dv", dv, heads)):
+    for name, r in (("o", o), ("dq", dq), ("dk", dk), ("dv", dv)):
         err = np.abs(out[name].astype(np.float64) - r)
-        tol = np.maximum(2e-2 * np.sqrt(hs), 8e-3 * np.abs(r))
+        tol = bf16_tol(r) + 2.0 ** -8 * np.abs(r)
         assert np.all(np.isfinite(out[name])) and np.all(err <= tol), (name, float(err.max()), float((err / tol).max()))

@@ -1,16 +1,13 @@
 """bf16 mode: HIP path vs the CPU oracle (which reads the same bf16-rounded inputs
 up-cast to fp32 and is not rounded at the end).
 
-Tolerance on o, dq, dk, dv: |err| <= max(2e-2, 5e-3 * |ref|) per element, i.e. the
-stated absolute 2e-2 wherever |ref| <= 4.  Beyond that an absolute bound cannot hold
-for a bf16 output: storing the exact value errs by up to |ref| * 2^-8 (0.0156 at 4,
-0.031 at 8, 0.0625 at 16), so the bound turns relative, 5e-3 = 2^-8 for the output
-rounding plus 1.1e-3 for the bf16 rounding of P and dS ahead of the MFMAs.  Values
-above 4 occur in dk, dv at the first keys of a group, mostly under GQA where several
-heads' gradients are summed; o and dq must meet the plain 2e-2.  Under GQA with r query
-heads per kv head, dk and dv are sums of r per-head gradients that each carry their own
-operand rounding, so their absolute term is 2e-2 * sqrt(r) (r = 1: the stated bound).
-lse is an fp32 output: <= 2e-3."""
+Tolerance on o, dq, dk, dv, per element: |err| <= 2e-2 + half-ulp_bf16(ref).  The stated
+bound is max-abs 2e-2; the second term is what storing the exact result as bf16 costs by
+itself (0.0078 for 2 <= |ref| < 4, 0.031 for 8 <= |ref| < 16; such values occur in dk, dv at
+the first keys of a group, where P is close to 1 for many queries, and under GQA where
+several heads' gradients are summed).  The bound carries no allowance for the number of
+heads or terms summed.  o and dq never leave the binades where the plain 2e-2 holds and
+are also held to it.  lse is an fp32 output: <= 2e-3."""
 import numpy as np
 import pytest
 
@@ -18,37 +15,16 @@ from oracle import s2attn_oracle as orc
 from paper_2309_12307_amd import inputs
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-2
-TOL_LSE = 2e-3
-
-
-RTOL = 5e-3
-
-
-def elementwise_tol(ref, heads_summed=1):
-    return np.maximum(TOL * np.sqrt(heads_summed), RTOL * np.abs(ref))
-
-
-def check_tensor(name, got, ref, heads_summed=1):
-    err = np.abs(got.astype(np.float64) - ref)
-    assert np.all(np.isfinite(got)), name
-    bad = err > elementwise_tol(ref, heads_summed)
-    if bad.any():
-        idx = np.unravel_index(np.argmax(err * bad), err.shape)
-        raise AssertionError(f"{name}: {bad.sum()} elements over tolerance; worst at {idx}: "
-                             f"got {got[idx]}, ref {ref[idx]}, err {err[idx]}")
-    return float(err.max())
 
 
 def compare(out, ref):
+    from gpu_util import TOL_BF16, TOL_LSE, check_bf16_tensor
     o, lse, dq, dk, dv = ref
     e_lse = np.abs(out["lse"] - lse).max()
     assert np.isfinite(e_lse) and e_lse <= TOL_LSE, ("lse", e_lse)
-    r_heads = o.shape[2] // dk.shape[2]      # query heads summed into each kv head's gradient
-    errs = {name: check_tensor(name, out[name], r, hs)
-            for name, r, hs in (("o", o, 1), ("dq", dq, 1), ("dk", dk, r_heads), ("dv", dv, r_heads))}
-    # o and dq never reach the binades where the bound is relaxed
-    assert errs["o"] <= TOL and errs["dq"] <= TOL, errs
+    errs = {name: check_bf16_tensor(name, out[name], r)[0]
+            for name, r in (("o", o), ("dq", dq), ("dk", dk), ("dv", dv))}
+    assert errs["o"] <= TOL_BF16 and errs["dq"] <= TOL_BF16, errs
     return errs
 
 
@@ -111,6 +87,40 @@ def test_variant2_split_wrap_group(shape):
     inp = inputs.make_inputs(B, N, H, Hkv, D, seed=181, dtype="bf16")
     out = run_hip(inp, G, "bf16", wrap_variant=binding.WRAP_SPLIT)
     ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, variant2=True)
+    compare(out, ref)
+
+
+# Variant 2 where the split G - shift is not a multiple of the 128-key tile of the dK/dV
+# kernels (64 mod 128, or inside a 64-row run), with partial last tiles, GQA and MQA.
+@pytest.mark.parametrize("shape,shift", [
+    ((1, 1536, 4, 4, 128, 384), None),     # split at 192
+    ((1, 1024, 4, 2, 128, 256), 64),       # split at 192
+    ((1, 1024, 4, 2, 128, 256), 192),      # split at 64
+    ((1, 2048, 4, 4, 128, 512), 64),       # split at 448: the first block spans 3.5 key tiles
+    ((1, 1000, 4, 2, 128, 500), None),     # partial tiles, split at 250
+    ((1, 1024, 2, 2, 128, 256), 100),      # split at 156, wrap point inside a tile
+    ((1, 400, 2, 1, 128, 200), 3),         # MQA; second block of 3 rows
+    ((1, 390, 2, 2, 128, 130), 129),       # first block of one row
+    ((2, 1280, 4, 4, 128, 640), None),     # five tiles, split at 320; batch 2
+])
+def test_variant2_split_not_on_a_tile_boundary(shape, shift):
+    from gpu_util import run_hip
+    from paper_2309_12307_amd import binding
+    B, N, H, Hkv, D, G = shape
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=182 + sum(shape), dtype="bf16")
+    kw = {} if shift is None else dict(shift=shift)
+    out = run_hip(inp, G, "bf16", wrap_variant=binding.WRAP_SPLIT, **kw)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, variant2=True, shift=shift)
+    compare(out, ref)
+
+
+def test_variant2_with_all_heads_shifted_and_head_shards():
+    from gpu_util import run_hip
+    from paper_2309_12307_amd import binding
+    B, N, H, Hkv, D, G = 1, 1152, 4, 2, 128, 384
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=183, dtype="bf16")
+    out = run_hip(inp, G, "bf16", wrap_variant=binding.WRAP_SPLIT, shift_rule=binding.SHIFT_ALL)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, variant2=True, shift_heads="all")
     compare(out, ref)
 
 
@@ -216,3 +226,15 @@ def test_config_c2_full_tensors():
     ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], cfg.G, dtype=np.float32)
     errs = compare(out, ref)
     print("C2 max-abs errors", errs)
+
+
+def test_config_c2_variant2_full_tensors():
+    """Same layer with the wrap-around group split (Appendix B.3 Variant 2), on the aligned
+    kernels (split at 1024)."""
+    from gpu_util import run_hip
+    from paper_2309_12307_amd import binding
+    cfg = inputs.CONFIGS["C2"]
+    inp = inputs.make_config_inputs(cfg)
+    out = run_hip(inp, cfg.G, "bf16", wrap_variant=binding.WRAP_SPLIT)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], cfg.G, variant2=True, dtype=np.float32)
+    compare(out, ref)

@@ -138,6 +138,51 @@ def test_roll_free_mask_formulation_agrees():
         assert np.abs(o1 - o2).max() < 1e-12 and np.abs(l1 - l2).max() < 1e-12
 
 
+@pytest.mark.parametrize("shift", [3, 1, 7])
+def test_roll_free_mask_formulation_agrees_at_a_custom_shift(shift):
+    B, N, H, Hkv, D, G = 1, 32, 4, 2, 4, 8
+    q, k, v, _ = rand_problem(B, N, H, Hkv, D, 41)
+    for heads in ("second_half", "all"):
+        o1, l1 = orc.s2attn_fwd(q, k, v, G, shift=shift, shift_heads=heads)
+        o2, l2 = orc.s2attn_fwd_masked(q, k, v, G, shift=shift, shift_heads=heads)
+        assert np.abs(o1 - o2).max() < 1e-12 and np.abs(l1 - l2).max() < 1e-12
+
+
+def test_custom_shift_and_all_heads_rule_are_textbook_attention_on_their_token_ranges():
+    """Shift s on every head: group g is tokens [g*G + s, (g+1)*G + s) mod N, each a plain
+    causal attention (token ranges written out here, not taken from the oracle)."""
+    B, N, H, Hkv, D, G, s = 1, 40, 2, 2, 8, 10, 3
+    q, k, v, _ = rand_problem(B, N, H, Hkv, D, 42)
+    o, _ = orc.s2attn_fwd(q, k, v, G, shift=s, shift_heads="all")
+    for h in range(H):
+        for g in range(N // G):
+            tok = (np.arange(G) + g * G + s) % N
+            ref = textbook_causal(q[0, tok, h], k[0, tok, h], v[0, tok, h], 1 / np.sqrt(D))
+            assert np.abs(o[0, tok, h] - ref).max() < 1e-12
+
+
+def test_shift_direction_variant1_gives_the_same_result():
+    """Appendix B.3 Variant 1 rolls the shifted heads by +G/2 going in and -G/2 coming out
+    (the opposite direction).  The groups are the same token sets in the same order, only
+    numbered differently, so outputs and gradients equal the default method's."""
+    B, N, H, Hkv, D, G = 2, 32, 4, 2, 4, 8
+    q, k, v, do = rand_problem(B, N, H, Hkv, D, 43)
+    ref = orc.s2attn_fwd_bwd(q, k, v, do, G)
+    # the oracle rolls by -shift in and +shift out: shift = -G/2 is Variant 1
+    var1 = orc.s2attn_fwd_bwd(q, k, v, do, G, shift=-(G // 2))
+    for a, b in zip(ref, var1):
+        assert np.abs(a - b).max() < 1e-13
+    # written out with numpy alone for one shifted head: roll by +G/2, plain block-diagonal
+    # causal attention, roll back by -G/2
+    h = H - 1
+    qr, kr, vr = (np.roll(x[0, :, hh], G // 2, axis=0) for x, hh in ((q, h), (k, h // 2), (v, h // 2)))
+    out = np.empty_like(qr)
+    for g in range(N // G):
+        sl = slice(g * G, (g + 1) * G)
+        out[sl] = textbook_causal(qr[sl], kr[sl], vr[sl], 1 / np.sqrt(D))
+    assert np.abs(np.roll(out, -(G // 2), axis=0) - ref[0][0, :, h]).max() < 1e-12
+
+
 def test_closed_forms():
     B, N, H, Hkv, D, G = 1, 32, 4, 4, 4, 8
     q, k, v, _ = rand_problem(B, N, H, Hkv, D, 5)
@@ -221,14 +266,13 @@ def test_variant2_splits_the_wrap_group():
 
 
 # ---------------------------------------------------------------- backward pins
-@pytest.mark.parametrize("Hkv", [4, 2, 1])
-def test_gradients_match_central_finite_differences(Hkv):
-    B, N, H, D, G = 2, 16, 4, 4, 8
-    q, k, v, do = rand_problem(B, N, H, Hkv, D, 10 + Hkv)
-    _, _, dq, dk, dv = orc.s2attn_fwd_bwd(q, k, v, do, G)
+def finite_difference_check(q, k, v, do, G, **kw):
+    """Central differences of L = sum(o * do) in every element of q, k, v against the
+    oracle's softmax-Jacobian gradients, for the oracle options in kw."""
+    _, _, dq, dk, dv = orc.s2attn_fwd_bwd(q, k, v, do, G, **kw)
 
     def loss(q_, k_, v_):
-        o, _ = orc.s2attn_fwd(q_, k_, v_, G)
+        o, _ = orc.s2attn_fwd(q_, k_, v_, G, **kw)
         return float((o * do).sum())
 
     eps = 1e-5
@@ -245,7 +289,27 @@ def test_gradients_match_central_finite_differences(Hkv):
             x[idx] = old
             num[idx] = (lp - lm) / (2 * eps)
         err = np.abs(num - gx).max() / max(1.0, np.abs(num).max())
-        assert err < 1e-6, (name, err)
+        assert err < 1e-6, (name, kw, err)
+
+
+@pytest.mark.parametrize("Hkv", [4, 2, 1])
+def test_gradients_match_central_finite_differences(Hkv):
+    B, N, H, D, G = 2, 16, 4, 4, 8
+    q, k, v, do = rand_problem(B, N, H, Hkv, D, 10 + Hkv)
+    finite_difference_check(q, k, v, do, G)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(variant2=True),                          # Appendix B.3 Variant 2: the wrap group split in two
+    dict(shift=3),                                # a shift other than G/2
+    dict(shift=3, variant2=True),                 # ... with the split at G - shift = 5
+    dict(shift_heads="all"),                      # every head shifted (Section 4.3 ablation)
+    dict(shift_heads="none"),
+])
+def test_gradients_of_the_oracle_options_match_finite_differences(kw):
+    B, N, H, Hkv, D, G = 1, 16, 4, 2, 4, 8
+    q, k, v, do = rand_problem(B, N, H, Hkv, D, 40)
+    finite_difference_check(q, k, v, do, G, **kw)
 
 
 def test_gradients_match_autograd_through_library_attention():
@@ -320,3 +384,47 @@ def test_fp32_and_fp64_oracle_agree_at_the_benchmark_group_size():
     b = orc.s2attn_group_slice(q, k, v, do, G, 0, 0, 0, shift=0, dtype=np.float64)
     for name in ("o", "lse", "dq", "dk", "dv"):
         assert np.abs(a[name] - b[name]).max() < 1e-5, name
+
+
+def test_fp32_oracle_against_fp64_definition_at_the_100k_group_size():
+    """G = 25600, D = 128 (the group size of the 100k-token configuration, where the GPU
+    parity tests use the fp32 oracle): the fp32 run of one group against fp64 arithmetic
+    written out here block by block from Equation 1 and the softmax Jacobian -- all of lse,
+    o and dq on a row block in the middle and one at the end, dk and dv on the last keys
+    (whose gradients need only the last rows) and on the first keys (all rows)."""
+    G, D, scale = 25600, 128, 1 / np.sqrt(128)
+    r = np.random.default_rng(32)
+    q, k, v, do = (r.standard_normal((G, D)).astype(np.float32) for _ in range(4))
+    P, o, lse = orc.dense_group_attention(q, k, v, np.float32(scale))
+    dq, dk, dv = orc.dense_group_attention_grad(P, q, k, v, do, np.float32(scale))
+    assert o.dtype == np.float32 and dq.dtype == np.float32
+    del P
+    q64, k64, v64, do64 = (x.astype(np.float64) for x in (q, k, v, do))
+
+    def rows_fp64(i0, i1):
+        S = scale * (q64[i0:i1] @ k64.T)
+        S[np.arange(i0, i1)[:, None] < np.arange(G)[None, :]] = -np.inf
+        m = S.max(1, keepdims=True)
+        l = np.exp(S - m).sum(1, keepdims=True)
+        Pb = np.exp(S - m) / l
+        ob = Pb @ v64
+        dP = do64[i0:i1] @ v64.T
+        dS = Pb * (dP - (Pb * dP).sum(1, keepdims=True))
+        return Pb, dS, ob, (m + np.log(l))[:, 0], scale * (dS @ k64)
+
+    kb_first, kb_last = slice(0, 32), slice(G - 32, G)
+    dk_first = np.zeros((32, D)); dv_first = np.zeros((32, D))
+    step = 1600
+    for i0 in range(0, G, step):
+        Pb, dS, ob, lb, dqb = rows_fp64(i0, i0 + step)
+        assert np.abs(lse[i0:i0 + step] - lb).max() < 2e-5
+        if i0 in (12800, G - step):
+            assert np.abs(o[i0:i0 + step] - ob).max() < 2e-5
+            assert np.abs(dq[i0:i0 + step] - dqb).max() < 2e-5
+        dv_first += Pb[:, kb_first].T @ do64[i0:i0 + step]
+        dk_first += scale * (dS[:, kb_first].T @ q64[i0:i0 + step])
+        if i0 == G - step:
+            assert np.abs(dv[kb_last] - Pb[:, kb_last].T @ do64[i0:i0 + step]).max() < 2e-5
+            assert np.abs(dk[kb_last] - scale * (dS[:, kb_last].T @ q64[i0:i0 + step])).max() < 2e-5
+    assert np.abs(dv[kb_first] - dv_first).max() < 5e-5
+    assert np.abs(dk[kb_first] - dk_first).max() < 5e-5
