@@ -104,6 +104,9 @@ def main():
                     help="C2 | C3 | C4 | C5 (bf16 configurations); a '-full' suffix (e.g. C3-full) runs plain "
                          "full causal attention of the same layer through the same kernels (G = N, no head "
                          "shifts), for the S2-Attn : full attention time ratio")
+    ap.add_argument("--bwd-algo", choices=["auto", "recompute", "stored"], default="auto",
+                    help="how the backward's dQ kernel gets dS: recomputed (what 'auto' picks) or stored by the "
+                         "dK/dV kernel in the workspace (2 bytes per (query, key) pair)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--operands", choices=["normal", "zero"], default="normal",
                     help="'zero' runs the same launches on all-zero q, k, v, dO: not the workload (the line says so "
@@ -144,10 +147,12 @@ def main():
     o = torch.empty_like(q)
     lse = torch.empty((cfg.B, cfg.H, cfg.N), dtype=torch.float32, device="cuda")
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-    ws = torch.empty(binding.bwd_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.Hkv, cfg.D, cfg.G), dtype=torch.uint8,
-                     device="cuda")
+    algo = {"auto": binding.BWD_AUTO, "recompute": binding.BWD_RECOMPUTE, "stored": binding.BWD_STORED_DS}[args.bwd_algo]
     p_fwd = binding.make_params(q, k, v, o, lse, cfg.G, shift_rule=rule)
-    p_bwd = binding.make_params(q, k, v, o, lse, cfg.G, dout=do, dq=dq, dk=dk, dv=dv, workspace=ws, shift_rule=rule)
+    p_bwd = binding.make_params(q, k, v, o, lse, cfg.G, dout=do, dq=dq, dk=dk, dv=dv, shift_rule=rule, bwd_algo=algo)
+    ws = torch.empty(binding.bwd_workspace_bytes_ex(p_bwd), dtype=torch.uint8, device="cuda")
+    p_bwd = binding.make_params(q, k, v, o, lse, cfg.G, dout=do, dq=dq, dk=dk, dv=dv, workspace=ws, shift_rule=rule,
+                                bwd_algo=algo)
     stream = torch.cuda.current_stream().cuda_stream
     ev = HipEvents()
 
@@ -217,7 +222,10 @@ def main():
                                f"D={cfg.D} G={cfg.G} " +
                                ("no head shifts (full causal attention)" if full
                                 else f"shift={cfg.G // 2} on heads >= H/2"),
-                   "effective_tflop_per_step": flops_total / 1e12},
+                   "effective_tflop_per_step": flops_total / 1e12,
+                   "backward": "dS stored by the dK/dV kernel, read back by the dQ kernel" if args.bwd_algo == "stored"
+                               else "dS recomputed in the dQ kernel",
+                   "workspace_bytes": int(ws.numel())},
         "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS,
         "device_time_per_step": spread,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,

@@ -59,7 +59,9 @@ enum {
   S2ATTN_ERR_DEVICE = -10,     /* current device is not gfx950 */
   S2ATTN_ERR_LAUNCH = -11,     /* HIP reported a launch error */
   S2ATTN_ERR_TOO_LARGE = -12,  /* tensor too large for the index arithmetic, or over a fixed limit */
-  S2ATTN_ERR_STRIDE = -13      /* a stride is negative, misaligned or smaller than the extent it spans */
+  S2ATTN_ERR_STRIDE = -13,     /* a stride is negative, misaligned or smaller than the extent it spans */
+  /* -14 is reserved */
+  S2ATTN_ERR_ALGO = -15        /* S2ATTN_BWD_STORED_DS asked for a shape it does not cover */
 };
 
 enum { S2ATTN_BF16 = 0, S2ATTN_F32 = 1 };
@@ -77,6 +79,22 @@ enum {
 enum {
   S2ATTN_WRAP_JOINT = 0,  /* one causal group: the paper's default method */
   S2ATTN_WRAP_SPLIT = 2   /* "Variant 2": the two halves are separate groups */
+};
+
+/* How the backward's dQ kernel obtains dS = P * (dP - delta) (the gradient formulas are the same;
+ * the paper leaves the backward to autograd).  Measured on MI355X at the 7B-shaped N = 32768
+ * layer the two take the same time to within 2 %, so the default is the one without the large
+ * workspace. */
+enum {
+  S2ATTN_BWD_AUTO = 0,       /* the library's choice: currently S2ATTN_BWD_RECOMPUTE */
+  S2ATTN_BWD_RECOMPUTE = 1,  /* the dQ kernel recomputes S and dP: workspace of a few MB, 18 D flops
+                                executed per (query, key) pair for forward + backward */
+  S2ATTN_BWD_STORED_DS = 2   /* the dK/dV kernel stores dS (bf16, 2 bytes per pair) in the workspace and
+                                the dQ kernel reads it back: 14 D flops per pair, 4 bytes of HBM traffic
+                                per pair.  bf16, G % 128 == 0, shift % 64 == 0, (G - shift) % 128 == 0
+                                under Variant 2, no kv head serving shifted and unshifted query heads;
+                                otherwise S2ATTN_ERR_ALGO.  The workspace must hold the dS of at least
+                                one kv head beyond the row terms; kv heads then run in passes */
 };
 
 typedef struct s2attn_params {
@@ -114,19 +132,23 @@ typedef struct s2attn_params {
    * be odd. */
   int heads_total;
   int head_offset;
+  int bwd_algo;       /* S2ATTN_BWD_*; backward only */
 } s2attn_params;
 
 /* Pure host check of a parameter block (pointers, alignment, shapes, workspace
  * size when `backward` is non-zero).  Touches no GPU state. */
 S2ATTN_API int s2attn_check_args(const s2attn_params* p, int backward);
 
-/* Bytes of device workspace the backward needs: the fp32 row term
- * delta[b,h,t] = sum_d dout*o and a base-2 copy of lse, plus fp32 partial dk/dv when a kv head serves both
- * shifted and unshifted query heads (odd Hkv under the second-half rule). */
+/* Bytes of device workspace the backward needs, for the published defaults (shift G/2 on the
+ * second half of the heads): the fp32 row term delta[b,h,t] = sum_d dout*o and a base-2 copy of
+ * lse, plus fp32 partial dk/dv when a kv head serves both shifted and unshifted query heads
+ * (odd Hkv). */
 S2ATTN_API size_t s2attn_bwd_workspace_bytes(int B, int N, int H, int Hkv, int D, int G, int dtype);
 
 /* Same for a parameter block (accounts for its shift rule and head sharding, which decide
- * whether a kv head serves both kinds of query heads); 0 if the shape fields are invalid. */
+ * whether a kv head serves both kinds of query heads, and for bwd_algo: S2ATTN_BWD_STORED_DS
+ * adds room for dS, 2 bytes per in-group causal (query, key) pair of as many kv heads as fit
+ * into 16 GiB, at least one); 0 if the shape fields are invalid. */
 S2ATTN_API size_t s2attn_bwd_workspace_bytes_ex(const s2attn_params* p);
 
 /* Forward of Algorithm 1, bf16 tensors, fp32 accumulation, default shift G/2 on

@@ -16,6 +16,7 @@ LIB_PATH = os.environ.get("S2ATTN_LIB", os.path.join(_HERE, "libs2attn.so"))
 BF16, F32 = 0, 1
 SHIFT_SECOND_HALF, SHIFT_NONE, SHIFT_ALL = 0, 1, 2
 WRAP_JOINT, WRAP_SPLIT = 0, 2
+BWD_AUTO, BWD_RECOMPUTE, BWD_STORED_DS = 0, 1, 2
 
 EXPORTS = [
     "s2attn_check_args", "s2attn_bwd_workspace_bytes", "s2attn_fwd", "s2attn_bwd",
@@ -38,7 +39,7 @@ class S2AttnParams(ctypes.Structure):
         ("q_strides", ctypes.c_longlong * 3), ("k_strides", ctypes.c_longlong * 3),
         ("v_strides", ctypes.c_longlong * 3), ("dq_strides", ctypes.c_longlong * 3),
         ("dk_strides", ctypes.c_longlong * 3), ("dv_strides", ctypes.c_longlong * 3),
-        ("heads_total", ctypes.c_int), ("head_offset", ctypes.c_int),
+        ("heads_total", ctypes.c_int), ("head_offset", ctypes.c_int), ("bwd_algo", ctypes.c_int),
     ]
 
 
@@ -149,7 +150,8 @@ def effective_flops(B, N, H, D, G, which: int = 2) -> float:
 
 def make_params(q, k, v, o, lse, G, dout=None, dq=None, dk=None, dv=None, workspace=None,
                 shift=-1, shift_rule=SHIFT_SECOND_HALF, wrap_variant=WRAP_JOINT, scale=0.0,
-                dtype=None, dims=None, strided=False, heads_total=0, head_offset=0) -> S2AttnParams:
+                dtype=None, dims=None, strided=False, heads_total=0, head_offset=0,
+                bwd_algo=BWD_AUTO) -> S2AttnParams:
     """strided=True takes the {batch, token, head} strides of q, k, v (and dq, dk, dv) from
     the tensors themselves, so views into a packed (B, N, 3, H, D) tensor can be passed."""
     if dims is None:
@@ -164,7 +166,7 @@ def make_params(q, k, v, o, lse, G, dout=None, dq=None, dk=None, dv=None, worksp
     p.B, p.N, p.H, p.Hkv, p.D, p.G = B, N, H, Hkv, D, G
     p.dtype = _dtype_code(q) if dtype is None else dtype
     p.shift, p.shift_rule, p.wrap_variant, p.scale = shift, shift_rule, wrap_variant, scale
-    p.heads_total, p.head_offset = heads_total, head_offset
+    p.heads_total, p.head_offset, p.bwd_algo = heads_total, head_offset, bwd_algo
     if strided:
         for name, t in (("q", q), ("k", k), ("v", v), ("dq", dq), ("dk", dk), ("dv", dv)):
             if t is None or isinstance(t, int):

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libs2attn.so")
 SOURCES = ["s2attn_api.hip", "s2attn_prepost.hip", "s2attn_f32.hip", "s2attn_bf16_fwd.hip", "s2attn_bf16_bwd.hip",
-           "s2attn_bf16_dkdv_split.hip"]
+           "s2attn_bf16_dkdv_split.hip", "s2attn_bf16_dq_spill.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-fno-honor-nans", "-mno-amdgpu-ieee",

@@ -53,6 +53,47 @@ size_t workspace_bytes_for(int B, int N, int H, int Hkv, int D, bool mixed) {
   return w;
 }
 
+// ---- stored-dS backward (tile-aligned bf16 shapes): the dK/dV kernel hands dS to the dQ
+// kernel through the workspace, one kv head's query heads after the other.
+constexpr size_t kDsSpillCap = (size_t)16 << 30;   // what the workspace queries ask for at most
+
+// Shapes the role-split dK/dV kernel (and so the stored-dS path) accepts.
+bool stored_ds_applies(const s2attn_params* p, int shift, int from) {
+  if (p->dtype != S2ATTN_BF16 || p->D != 128) return false;
+  if (p->G % 128 != 0 || shift % 64 != 0) return false;
+  if (p->wrap_variant == S2ATTN_WRAP_SPLIT && shift > 0 && (p->G - shift) % 128 != 0) return false;
+  return !kv_heads_mixed(p->H, p->Hkv, from);
+}
+
+// dS bytes of all query heads of one kv head: 2 bytes per (query, key) pair of the tiles at or
+// below the diagonal.
+size_t ds_bytes_per_kv_head(const s2attn_params* p) {
+  const size_t T = (size_t)p->G / 128;
+  return (size_t)p->B * (p->H / p->Hkv) * (p->N / p->G) * T * (T + 1) * s2::kDsBlobBytes;
+}
+
+// kv heads whose dS fits into `avail` bytes at a time (0: none).
+int ds_heads_per_pass(const s2attn_params* p, size_t avail) {
+  const size_t per_head = ds_bytes_per_kv_head(p);
+  const size_t n = avail / per_head;
+  return (int)std::min<size_t>(n, (size_t)p->Hkv);
+}
+
+// Workspace a parameter block asks for: the row terms (and partial sums), plus, when the block
+// asks for the stored-dS backward, room for the dS of as many kv heads as fit under the cap (at
+// least one).
+size_t workspace_bytes_wanted(const s2attn_params* p) {
+  const int shift = resolved_shift(p);
+  const int from = shifted_from(p, shift);
+  size_t w = workspace_bytes_for(p->B, p->N, p->H, p->Hkv, p->D, kv_heads_mixed(p->H, p->Hkv, from));
+  if (p->bwd_algo == S2ATTN_BWD_STORED_DS && stored_ds_applies(p, shift, from)) {
+    const size_t per_head = ds_bytes_per_kv_head(p);
+    const size_t heads = std::max<size_t>(1, std::min<size_t>((size_t)p->Hkv, kDsSpillCap / per_head));
+    w += heads * per_head;
+  }
+  return w;
+}
+
 bool strides_ok(const long long (&st)[3], int B, int heads, int D, int align) {
   if (st[0] == 0 && st[1] == 0 && st[2] == 0) return true;
   for (long long x : st)
@@ -86,6 +127,7 @@ int check_common(const s2attn_params* p, int backward) {
   if (p->dtype != S2ATTN_BF16 && p->dtype != S2ATTN_F32) return S2ATTN_ERR_DTYPE;
   if (p->shift_rule < S2ATTN_SHIFT_SECOND_HALF || p->shift_rule > S2ATTN_SHIFT_ALL) return S2ATTN_ERR_DTYPE;
   if (p->wrap_variant != S2ATTN_WRAP_JOINT && p->wrap_variant != S2ATTN_WRAP_SPLIT) return S2ATTN_ERR_DTYPE;
+  if (p->bwd_algo < S2ATTN_BWD_AUTO || p->bwd_algo > S2ATTN_BWD_STORED_DS) return S2ATTN_ERR_DTYPE;
   if (p->B <= 0 || p->N <= 0 || p->H <= 0 || p->Hkv <= 0 || p->D <= 0 || p->G <= 0) return S2ATTN_ERR_DIM;
   if (p->N % p->G != 0 || p->G % 2 != 0) return S2ATTN_ERR_GROUP;
   const int shift = resolved_shift(p);
@@ -130,10 +172,15 @@ int check_common(const s2attn_params* p, int backward) {
       if (!x) return S2ATTN_ERR_NULL;
       if (!aligned16(x)) return S2ATTN_ERR_ALIGN;
     }
-    const bool mixed = kv_heads_mixed(p->H, p->Hkv, shifted_from(p, shift));
+    const int from = shifted_from(p, shift);
+    const bool mixed = kv_heads_mixed(p->H, p->Hkv, from);
     const size_t need = workspace_bytes_for(p->B, p->N, p->H, p->Hkv, p->D, mixed);
     if (!p->workspace || p->workspace_bytes < need) return S2ATTN_ERR_WORKSPACE;
     if ((reinterpret_cast<uintptr_t>(p->workspace) & (kAlign - 1)) != 0) return S2ATTN_ERR_ALIGN;
+    if (p->bwd_algo == S2ATTN_BWD_STORED_DS) {
+      if (!stored_ds_applies(p, shift, from)) return S2ATTN_ERR_ALGO;
+      if (ds_heads_per_pass(p, p->workspace_bytes - need) == 0) return S2ATTN_ERR_WORKSPACE;
+    }
   }
   return S2ATTN_OK;
 }
@@ -186,6 +233,8 @@ s2::KArgs make_kargs(const s2attn_params* p) {
   a.mixed = kv_heads_mixed(p->H, p->Hkv, a.shifted_from) ? 1 : 0;
   a.ragged = (p->dtype == S2ATTN_BF16 &&
               (p->G % 128 != 0 || a.shift % 64 != 0 || (a.split < p->G && a.split % 128 != 0))) ? 1 : 0;
+  a.c_begin = 0;
+  a.c_count = p->Hkv;
   a.scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->D);
   a.scale_log2 = a.scale * 1.4426950408889634f;
   return a;
@@ -212,18 +261,16 @@ extern "C" {
 int s2attn_check_args(const s2attn_params* p, int backward) { return check_common(p, backward); }
 
 size_t s2attn_bwd_workspace_bytes(int B, int N, int H, int Hkv, int D, int G, int dtype) {
-  (void)G; (void)dtype;
-  if (B <= 0 || N <= 0 || H <= 0 || Hkv <= 0 || D <= 0 || H % Hkv != 0) return 0;
-  // sized for the default rule; the other rules never mix classes inside a kv head
-  const bool mixed = kv_heads_mixed(H, Hkv, H / 2);
-  return workspace_bytes_for(B, N, H, Hkv, D, mixed);
+  // the published defaults: shift G/2 on the second half of the heads, one causal wrap group
+  s2attn_params p = basic_params(nullptr, nullptr, nullptr, nullptr, nullptr, B, N, H, Hkv, D, G, dtype);
+  return s2attn_bwd_workspace_bytes_ex(&p);
 }
 
 size_t s2attn_bwd_workspace_bytes_ex(const s2attn_params* p) {
-  if (!p || p->B <= 0 || p->N <= 0 || p->H <= 0 || p->Hkv <= 0 || p->D <= 0 || p->G <= 0 || p->H % p->Hkv != 0)
+  if (!p || p->B <= 0 || p->N <= 0 || p->H <= 0 || p->Hkv <= 0 || p->D <= 0 || p->G <= 0 || p->H % p->Hkv != 0 ||
+      p->N % p->G != 0)
     return 0;
-  const bool mixed = kv_heads_mixed(p->H, p->Hkv, shifted_from(p, resolved_shift(p)));
-  return workspace_bytes_for(p->B, p->N, p->H, p->Hkv, p->D, mixed);
+  return workspace_bytes_wanted(p);
 }
 
 int s2attn_fwd_ex(const s2attn_params* p, void* stream) {
@@ -251,9 +298,27 @@ static int run_bwd(const s2attn_params* p, void* stream, void* const* events) {
   auto mark = [&](int i) {
     if (events && events[i]) (void)hipEventRecord(static_cast<hipEvent_t>(events[i]), st);
   };
+  // stored-dS backward: only on request (check_common has made sure that the shape allows it
+  // and that the workspace has room for the dS of at least one kv head beyond the row terms)
+  const size_t basic = workspace_bytes_for(p->B, p->N, p->H, p->Hkv, p->D, a.mixed != 0);
+  int ds_heads = 0;
+  if (p->bwd_algo == S2ATTN_BWD_STORED_DS) ds_heads = ds_heads_per_pass(p, p->workspace_bytes - basic);
   mark(0);
   if (s2::launch_delta(a, p->dtype, st) != 0) return S2ATTN_ERR_LAUNCH;
   mark(1);
+  if (ds_heads > 0) {
+    // kv heads in passes of ds_heads: dK/dV kernel (stores dS), then dQ from the stored dS
+    a.ds_spill = static_cast<char*>(p->workspace) + basic;
+    for (int c0 = 0; c0 < p->Hkv; c0 += ds_heads) {
+      a.c_begin = c0;
+      a.c_count = std::min(ds_heads, p->Hkv - c0);
+      if (s2::launch_bwd_dkdv_split_bf16(a, st) != 0) return S2ATTN_ERR_LAUNCH;
+      if (c0 + ds_heads >= p->Hkv) mark(2);
+      if (s2::launch_bwd_dq_spill_bf16(a, st) != 0) return S2ATTN_ERR_LAUNCH;
+    }
+    mark(3);
+    return S2ATTN_OK;
+  }
   rc = p->dtype == S2ATTN_F32 ? s2::launch_bwd_dkdv_f32(a, st) : s2::launch_bwd_dkdv_bf16(a, st);
   if (rc != 0) return S2ATTN_ERR_LAUNCH;
   mark(2);
@@ -319,6 +384,7 @@ const char* s2attn_strerror(int code) {
     case S2ATTN_ERR_LAUNCH: return "HIP kernel launch failed";
     case S2ATTN_ERR_TOO_LARGE: return "problem too large for the launch grid or index arithmetic";
     case S2ATTN_ERR_STRIDE: return "a stride is negative, misaligned or smaller than the extent it spans";
+    case S2ATTN_ERR_ALGO: return "S2ATTN_BWD_STORED_DS needs bf16, G a multiple of 128, shift (and a Variant 2 split) of 64 (128), and no kv head serving both head classes";
     default: return "unknown s2attn error code";
   }
 }

@@ -95,6 +95,16 @@ __device__ __forceinline__ void accumulate(f32x16 (&acc)[4], bf16x8 (&fa)[4], bf
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// 16 bytes per lane, written through to memory (system scope): the stored dS is not read
+// again by this kernel, and left to the L2's default policy it evicts the Q and dO tiles that
+// the workgroups of an XCD share (measured: 3.6 times the HBM reads).
+__device__ __forceinline__ void store_ds(char* dst, bf16x8 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(dst), "v"(v) : "memory");
+}
+
+// SPILL: role B also stores dS of every tile it finishes (bf16, the operand it feeds to the
+// dK product) for the dQ kernel, which then needs neither S nor dP again.
+template <bool SPILL>
 __global__ void __launch_bounds__(512, 1)
 bwd_dkdv_split_kernel(KArgs a, int T, int il, int n_rest) {
   __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
@@ -112,8 +122,8 @@ bwd_dkdv_split_kernel(KArgs a, int T, int il, int n_rest) {
   if (rest >= n_rest) return;
   const int NG = uni(a.N / a.G);
   const int gidx = uni(rest % NG); rest = uni(rest / NG);
-  const int c = uni(rest % a.Hkv);
-  const int b = uni(rest / a.Hkv);
+  const int c = uni(a.c_begin + rest % a.c_count);
+  const int b = uni(rest / a.c_count);
 
   const int h_lo = c * a.r;
   const int s = uni(h_lo >= a.shifted_from ? a.shift : 0);
@@ -250,6 +260,18 @@ bwd_dkdv_split_kernel(KArgs a, int T, int il, int n_rest) {
     // ------------------------------------------------------------------ role B
     int q_st = 0;                     // n mod 3
     f32x16 dp0 = zero16(), dp1 = zero16();   // delta - dP of the pending tile
+    // dS blobs of this workgroup: those of key tile jt of head h_lo, one after the other along
+    // the query tiles; the next head's are a whole (head, group-count) block further on
+    char* ds_lane = nullptr;
+    long long ds_head_stride = 0;
+    int hh_prev = 0, it_prev = -1;    // tile n - 1
+    if constexpr (SPILL) {
+      const long long per_group = ds_blobs_per_group(T);
+      const long long first = ((long long)(b * a.c_count * a.r + (h_lo - a.c_begin * a.r)) * NG + gidx) * per_group +
+                              ds_blob_index(T, jt, 0);
+      ds_lane = static_cast<char*>(a.ds_spill) + first * kDsBlobBytes + kb * 4096 + lane * 16;
+      ds_head_stride = (long long)NG * per_group * kDsBlobBytes;
+    }
     for (int n = 0; n <= n_iter; ++n) {
       const int o_st = n & 1;
       wait_vmcnt0();
@@ -286,6 +308,16 @@ bwd_dkdv_split_kernel(KArgs a, int T, int il, int n_rest) {
           dsf[2 * mb] = pack8(dx[0], dx[1], dx[2], dx[3], dx[4], dx[5], dx[6], dx[7]);
           dsf[2 * mb + 1] = pack8(dx[8], dx[9], dx[10], dx[11], dx[12], dx[13], dx[14], dx[15]);
         }
+        if constexpr (SPILL) {
+          // the four packed operands as they are: each store is 1 KB of consecutive bytes
+          char* dst = ds_lane + hh_prev * ds_head_stride + (long long)it_prev * kDsBlobBytes;
+#pragma unroll
+          for (int f = 0; f < 4; ++f)
+            store_ds(dst + 1024 * f, dsf[f]);
+        }
+      }
+      if constexpr (SPILL) {   // tile n becomes tile n - 1
+        if (++it_prev == nq) { it_prev = 0; ++hh_prev; }
       }
       if (has_cur) {
         // delta - dP of tile n: the accumulators start at delta (per query row = per register);
@@ -331,10 +363,13 @@ bool dkdv_split_applies(const KArgs& a) {
 int launch_bwd_dkdv_split_bf16(const KArgs& a, hipStream_t st) {
   const int NG = a.N / a.G;
   const int T = a.G / 128;
-  const int n_rest = a.B * a.Hkv * NG;
+  const int n_rest = a.B * a.c_count * NG;
   const int il = interleave_for(T, 32);   // 32 CUs per XCD, one workgroup each
   const int blocks = 8 * T * pad_to((n_rest + 7) / 8, il);
-  hipLaunchKernelGGL(bwd_dkdv_split_kernel, dim3(blocks), dim3(512), 0, st, a, T, il, n_rest);
+  if (a.ds_spill)
+    hipLaunchKernelGGL(bwd_dkdv_split_kernel<true>, dim3(blocks), dim3(512), 0, st, a, T, il, n_rest);
+  else
+    hipLaunchKernelGGL(bwd_dkdv_split_kernel<false>, dim3(blocks), dim3(512), 0, st, a, T, il, n_rest);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -19,6 +19,8 @@ struct KArgs {
   float* delta;                              // (B,H,N) fp32
   float* lse2;                               // (B,H,N) fp32: lse * log2(e), written by the pre-pass
   float* dkv_partial;                        // fp32 [2 tensors][2 classes][B,N,Hkv,D] or null
+  void* ds_spill;                            // bf16 dS tiles handed from the dK/dV kernel to the dQ kernel, or null
+  int c_begin, c_count;                      // kv heads [c_begin, c_begin + c_count) of this launch (spill path)
   TStride sq, sk, sv, sdq, sdk, sdv;         // q, k, v and their gradients may be strided views
   TStride so;                                // o and dout: contiguous (B,N,H,D)
   int B, N, H, Hkv, D, G;
@@ -81,6 +83,30 @@ __device__ __forceinline__ void decode_slot(int slot, int T, int il, int& y, int
   const int within = slot - chunk * span;
   rank = __builtin_amdgcn_readfirstlane(within / il);
   y = chunk * il + (within - rank * il);
+}
+
+// ---- dS hand-over between the two backward kernels (tile-aligned shapes only).
+// The dK/dV kernel stores dS = P * (dP - delta) of every (64 queries x 128 keys) tile it
+// visits as one 16 KB blob, exactly as its waves hold it: [key block kb 0..3][operand f 0..3]
+// [lane 0..63][8 bf16], where lane = 32 g + (key % 32) of the wave that owns keys
+// 32 kb .. 32 kb + 31, and element e of the lane's f-th packed operand is query
+// 32 (f / 2) + 16 (f % 2) + 8 (e / 4) + 4 g + (e % 4) of the tile.  Every store instruction
+// of a wave therefore writes 1 KB of consecutive bytes.  Seen as a matrix with one row per
+// key and the 64 queries along the columns in the order (f, g, e), the column index within
+// every 16 queries is the query index with bits 2 and 3 exchanged.  The dQ kernel reads the
+// blobs back instead of recomputing S and dP.
+// Blobs of one (batch, query head, group) are ordered by key tile jt (128 keys), then by
+// query tile it = 0, 1, ... counted from the diagonal (query rows 128 jt + 64 it ...); a key
+// tile has 2 (T - jt) query tiles when the group has T key tiles.
+constexpr int kDsBlobBytes = 64 * 128 * 2;
+__host__ __device__ inline long long ds_blobs_per_group(int T) { return (long long)T * (T + 1); }
+__host__ __device__ inline long long ds_blob_index(int T, int jt, int it) {
+  return (long long)jt * (2 * T - jt + 1) + it;
+}
+// Query row (within its 16) of column `col` (within its 16) of a blob, and back: bits 2 and 3
+// exchanged.
+__host__ __device__ inline int ds_col_query(int col) {
+  return (col & ~12) | ((col & 4) << 1) | ((col & 8) >> 1);
 }
 
 // Kernels built for partial tiles treat Variant 2 by running the two halves of the

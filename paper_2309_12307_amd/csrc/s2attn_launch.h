@@ -14,7 +14,9 @@ int launch_bwd_dkdv_bf16(const KArgs& a, hipStream_t st);  // delta must be read
 int launch_bwd_dq_bf16(const KArgs& a, hipStream_t st);
 // two-waves-per-SIMD dK/dV kernel for the shapes dkdv_split_applies() accepts
 bool dkdv_split_applies(const KArgs& a);
-int launch_bwd_dkdv_split_bf16(const KArgs& a, hipStream_t st);
+int launch_bwd_dkdv_split_bf16(const KArgs& a, hipStream_t st);   // a.ds_spill set: also stores the dS blobs
+// dQ from the dS blobs the dK/dV kernel stored (same shapes as dkdv_split_applies)
+int launch_bwd_dq_spill_bf16(const KArgs& a, hipStream_t st);
 
 // delta[b,h,t] = sum_d dout[b,t,h,d] * o[b,t,h,d], fp32
 int launch_delta(const KArgs& a, int dtype, hipStream_t st);

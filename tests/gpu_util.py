@@ -16,10 +16,12 @@ def to_np(t: torch.Tensor) -> np.ndarray:
     return t.float().cpu().numpy()
 
 
-def run_hip(inp: dict, G: int, dtype: str, backward=True, **ex):
+def run_hip(inp: dict, G: int, dtype: str, backward=True, ws_bytes=None, **ex):
     """inp: dict from inputs.make_inputs.  Returns dict of numpy float32 arrays
     o, lse, dq, dk, dv (gradients only when backward).  Extra keyword arguments
-    (shift, shift_rule, wrap_variant, scale) go through the *_ex entry points."""
+    (shift, shift_rule, wrap_variant, scale, bwd_algo) go through the *_ex entry points.
+    ws_bytes: workspace size to pass instead of what the library asks for; a callable gets
+    the library's size for the recomputing backward (the row terms) and the size it asks for."""
     bf = dtype == "bf16"
     q = to_dev(inp["q"], inp.get("q_bits") if bf else None)
     k = to_dev(inp["k"], inp.get("k_bits") if bf else None)
@@ -39,12 +41,18 @@ def run_hip(inp: dict, G: int, dtype: str, backward=True, **ex):
         dq = torch.full_like(q, float("nan"))
         dk = torch.full_like(k, float("nan"))
         dv = torch.full_like(v, float("nan"))
-        nbytes = binding.bwd_workspace_bytes(B, N, H, Hkv, D, G, binding.BF16 if bf else binding.F32)
-        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-        if ex:
+        if ex or ws_bytes is not None:
+            p = binding.make_params(q, k, v, o, lse, G, dout=do, dq=dq, dk=dk, dv=dv, **ex)
+            nbytes = binding.bwd_workspace_bytes_ex(p)
+            if ws_bytes is not None:
+                p_min = binding.make_params(q, k, v, o, lse, G, **{**ex, "bwd_algo": binding.BWD_RECOMPUTE})
+                nbytes = ws_bytes(binding.bwd_workspace_bytes_ex(p_min), nbytes) if callable(ws_bytes) else ws_bytes
+            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
             p = binding.make_params(q, k, v, o, lse, G, dout=do, dq=dq, dk=dk, dv=dv, workspace=ws, **ex)
             binding.s2attn_bwd_ex(p)
         else:
+            nbytes = binding.bwd_workspace_bytes(B, N, H, Hkv, D, G, binding.BF16 if bf else binding.F32)
+            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
             binding.s2attn_bwd(q, k, v, o, do, lse, dq, dk, dv, ws, G)
         torch.cuda.synchronize()
         out.update(dq=to_np(dq), dk=to_np(dk), dv=to_np(dv))

@@ -56,7 +56,15 @@ def params(**kw):
     p.scale = 0.0
     p.heads_total = kw.get("heads_total", 0)
     p.head_offset = kw.get("head_offset", 0)
+    p.bwd_algo = kw.get("bwd_algo", 0)
     return p
+
+
+def ds_bytes(B, N, H, G, heads=None):
+    """Bytes of stored dS for `heads` query heads (default all): 16 KB per (64 query x 128 key)
+    tile at or below the diagonal, T (T + 1) of them per (head, group) with T = G / 128."""
+    T = G // 128
+    return B * (H if heads is None else heads) * (N // G) * T * (T + 1) * 16384
 
 
 def test_validator_accepts_benchmark_shapes():
@@ -137,6 +145,9 @@ def test_workspace_size_follows_the_shard():
     assert binding.bwd_workspace_bytes_ex(p) == 2 * 8 * 1024 * 4
     p = params(H=8, Hkv=2, heads_total=20, head_offset=4)
     assert binding.bwd_workspace_bytes_ex(p) == 2 * 8 * 1024 * 4 + 4 * 1024 * 2 * 128 * 4
+    # the stored-dS backward adds room for dS
+    p = params(H=8, Hkv=2, heads_total=16, head_offset=4, bwd_algo=binding.BWD_STORED_DS)
+    assert binding.bwd_workspace_bytes_ex(p) == 2 * 8 * 1024 * 4 + ds_bytes(1, 1024, 8, 256)
     # whole layer: same as the plain query
     p = params()
     assert binding.bwd_workspace_bytes_ex(p) == binding.bwd_workspace_bytes(1, 1024, 4, 4, 128, 256)
@@ -157,11 +168,39 @@ def test_forward_check_ignores_backward_fields():
 
 
 def test_workspace_size():
-    # delta and base-2 lse: 2 * B*H*N floats (each rounded to 256 bytes)
-    assert binding.bwd_workspace_bytes(1, 32768, 32, 32, 128, 8192) == 2 * 32 * 32768 * 4
+    rows = 2 * 32 * 32768 * 4      # delta and base-2 lse: 2 * B*H*N floats (each rounded to 256 bytes)
+    assert binding.bwd_workspace_bytes(1, 32768, 32, 32, 128, 8192) == rows
     # MQA: one kv head serves shifted and unshifted heads -> fp32 partials too
     w = binding.bwd_workspace_bytes(1, 256, 4, 1, 64, 64, binding.F32)
     assert w == 2 * 4 * 256 * 4 + 4 * 256 * 64 * 4
+    # stored-dS backward.  The 7B-shaped layer at N = 32768: dS of all 32 heads (8.7 GB, under the
+    # 16 GiB the query asks for at most)
+    st = binding.BWD_STORED_DS
+    p = params(B=1, N=32768, H=32, Hkv=32, D=128, G=8192, bwd_algo=st)
+    assert binding.bwd_workspace_bytes_ex(p) == rows + ds_bytes(1, 32768, 32, 8192)
+    # GQA layer (17.4 GB of dS in all): 7 of the 8 kv heads at a time
+    per_kv_head = ds_bytes(1, 32768, 64, 8192, heads=8)
+    p = params(B=1, N=32768, H=64, Hkv=8, D=128, G=8192, bwd_algo=st)
+    assert binding.bwd_workspace_bytes_ex(p) == 2 * rows + 7 * per_kv_head and 2 ** 34 // per_kv_head == 7
+    # 100k-token layer: 6 heads at a time
+    p = params(B=1, N=102400, H=32, Hkv=32, D=128, G=25600, bwd_algo=st)
+    assert binding.bwd_workspace_bytes_ex(p) == 2 * 32 * 102400 * 4 + 6 * ds_bytes(1, 102400, 32, 25600, heads=1)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(bwd_algo=2), 0),
+    (dict(bwd_algo=3), -9),
+    (dict(bwd_algo=2, G=200, N=1000), -15),                    # unaligned group
+    (dict(bwd_algo=2, shift=32), -15),
+    (dict(bwd_algo=2, H=2, Hkv=1), -15),                       # the kv head serves both head classes
+    (dict(bwd_algo=2, dtype=1, D=64), -15),
+    (dict(bwd_algo=2, G=384, N=1536, wrap_variant=2), -15),    # Variant 2 split at 192
+    (dict(bwd_algo=2, wrap_variant=2), 0),
+    (dict(bwd_algo=2, workspace_bytes=2 * 4 * 1024 * 4), -8),  # row terms only: no room for one kv head's dS
+    (dict(bwd_algo=0, workspace_bytes=2 * 4 * 1024 * 4), 0),   # the default needs the row terms only
+])
+def test_backward_algorithm_field(kw, code):
+    assert binding.check_args(params(**kw), True) == code
 
 
 def test_missing_library_is_an_error(monkeypatch, tmp_path):

@@ -50,6 +50,57 @@ def test_shapes(shape):
     compare(out, ref)
 
 
+# The two ways the backward gets dS into its dQ kernel (stored by the dK/dV kernel, or
+# recomputed) on tile-aligned shapes; everything else in this file runs the default, which
+# recomputes.
+ALIGNED_SHAPES = [
+    (1, 512, 2, 2, 128, 128),      # one key tile per group: only diagonal tiles
+    (2, 1024, 4, 4, 128, 256),     # batch 2
+    (1, 2048, 8, 2, 128, 1024),    # 4 query heads per kv head
+    (1, 1536, 4, 2, 128, 384),     # three key tiles
+    (1, 640, 2, 2, 128, 640),      # one group, five key tiles
+]
+
+
+@pytest.mark.parametrize("shape", ALIGNED_SHAPES)
+@pytest.mark.parametrize("algo", ["recompute", "stored"])
+def test_backward_algorithms(shape, algo):
+    from gpu_util import run_hip
+    from paper_2309_12307_amd import binding
+    B, N, H, Hkv, D, G = shape
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=sum(shape), dtype="bf16")
+    out = run_hip(inp, G, "bf16", bwd_algo=binding.BWD_RECOMPUTE if algo == "recompute" else binding.BWD_STORED_DS)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G)
+    compare(out, ref)
+
+
+@pytest.mark.parametrize("heads_at_a_time", [1, 3])
+def test_stored_ds_backward_in_several_passes(heads_at_a_time):
+    """A workspace with room for the dS of only some kv heads: the backward runs the kv heads
+    in passes over the same dS area."""
+    from gpu_util import run_hip
+    from paper_2309_12307_amd import binding
+    B, N, H, Hkv, D, G = 1, 1024, 8, 4, 128, 256
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=77, dtype="bf16")
+    size = lambda rows, wanted: rows + (wanted - rows) // Hkv * heads_at_a_time + 100
+    out = run_hip(inp, G, "bf16", ws_bytes=size, bwd_algo=binding.BWD_STORED_DS)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G)
+    compare(out, ref)
+
+
+def test_stored_ds_backward_with_variant2_and_custom_shift():
+    from gpu_util import run_hip
+    from paper_2309_12307_amd import binding
+    B, N, H, Hkv, D, G = 1, 1536, 4, 2, 128, 512
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=78, dtype="bf16")
+    for kw, okw in ((dict(wrap_variant=binding.WRAP_SPLIT), dict(variant2=True)),
+                    (dict(wrap_variant=binding.WRAP_SPLIT, shift=128), dict(variant2=True, shift=128)),
+                    (dict(shift=192, shift_rule=binding.SHIFT_ALL), dict(shift=192, shift_heads="all"))):
+        out = run_hip(inp, G, "bf16", bwd_algo=binding.BWD_STORED_DS, **kw)
+        ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, **okw)
+        compare(out, ref)
+
+
 def test_full_causal_attention_mode():
     from gpu_util import run_hip
     from paper_2309_12307_amd import binding
@@ -226,6 +277,17 @@ def test_config_c2_full_tensors():
     ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], cfg.G, dtype=np.float32)
     errs = compare(out, ref)
     print("C2 max-abs errors", errs)
+
+
+def test_config_c2_full_tensors_stored_ds_backward():
+    from gpu_util import run_hip
+    from paper_2309_12307_amd import binding
+    cfg = inputs.CONFIGS["C2"]
+    inp = inputs.make_config_inputs(cfg)
+    out = run_hip(inp, cfg.G, "bf16", bwd_algo=binding.BWD_STORED_DS)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], cfg.G, dtype=np.float32)
+    errs = compare(out, ref)
+    print("C2 (stored-dS backward) max-abs errors", errs)
 
 
 def test_config_c2_variant2_full_tensors():
