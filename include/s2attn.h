@@ -60,7 +60,7 @@ enum {
   S2ATTN_ERR_LAUNCH = -11,     /* HIP reported a launch error */
   S2ATTN_ERR_TOO_LARGE = -12,  /* tensor too large for the index arithmetic, or over a fixed limit */
   S2ATTN_ERR_STRIDE = -13,     /* a stride is negative, misaligned or smaller than the extent it spans */
-  /* -14 is reserved */
+  S2ATTN_ERR_SCRATCH = -14,    /* s2attn_bwd_ex_static: the problem needs more than S2ATTN_STATIC_SCRATCH_BYTES */
   S2ATTN_ERR_ALGO = -15        /* S2ATTN_BWD_STORED_DS asked for a shape it does not cover */
 };
 
@@ -175,6 +175,22 @@ S2ATTN_API int s2attn_bwd_f32(const float* q, const float* k, const float* v, co
  * patterns), wrap-group variant (Appendix B.3) and scale come from the block. */
 S2ATTN_API int s2attn_fwd_ex(const s2attn_params* p, void* stream);
 S2ATTN_API int s2attn_bwd_ex(const s2attn_params* p, void* stream);
+
+/* For callers that cannot allocate device memory or carry a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): s2attn_bwd_ex with the
+ * workspace replaced by a device array of S2ATTN_STATIC_SCRATCH_BYTES that is part of the
+ * library image (each GPU holds its own copy until the process ends).  p->workspace and
+ * p->workspace_bytes are ignored; everything else, results included, is as in s2attn_bwd_ex.
+ * It always runs the recomputing backward (p->bwd_algo is ignored).
+ * The call allocates nothing and frees nothing.  A problem whose
+ * s2attn_bwd_workspace_bytes_ex (without stored dS) exceeds S2ATTN_STATIC_SCRATCH_BYTES
+ * (for MHA and even Hkv: B * H * N > 2097152 rows) is refused with S2ATTN_ERR_SCRATCH before anything is launched.
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU
+ * (different streams, several host threads) race on it and must be serialised by the caller;
+ * nothing in it needs to start at zero, and a call leaves nothing behind that a later call
+ * reads. */
+#define S2ATTN_STATIC_SCRATCH_BYTES (16u << 20)
+S2ATTN_API int s2attn_bwd_ex_static(const s2attn_params* p, void* stream);
 
 /* Measurement aid: s2attn_bwd_ex that also records up to four caller-owned HIP events
  * (hipEvent_t passed as void*, entries may be NULL) on `stream`: events[0] before the

@@ -22,7 +22,7 @@ EXPORTS = [
     "s2attn_check_args", "s2attn_bwd_workspace_bytes", "s2attn_fwd", "s2attn_bwd",
     "s2attn_fwd_f32", "s2attn_bwd_f32", "s2attn_fwd_ex", "s2attn_bwd_ex",
     "s2attn_strerror", "s2attn_effective_flops", "s2attn_bwd_ex_marked",
-    "s2attn_bwd_workspace_bytes_ex",
+    "s2attn_bwd_workspace_bytes_ex", "s2attn_bwd_ex_static",
 ]
 
 
@@ -76,7 +76,7 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.argtypes = [vp] * 9 + [vp, sz] + [i] * 6 + [vp]
             f.restype = i
-        for name in ("s2attn_fwd_ex", "s2attn_bwd_ex"):
+        for name in ("s2attn_fwd_ex", "s2attn_bwd_ex", "s2attn_bwd_ex_static"):
             f = getattr(L, name)
             f.argtypes = [ctypes.POINTER(S2AttnParams), vp]
             f.restype = i
@@ -205,6 +205,14 @@ def s2attn_fwd_ex(p: S2AttnParams, stream=None) -> None:
 
 def s2attn_bwd_ex(p: S2AttnParams, stream=None) -> None:
     _check(lib().s2attn_bwd_ex(ctypes.byref(p), _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def s2attn_bwd_ex_static(p: S2AttnParams, stream=None) -> None:
+    """s2attn_bwd_ex on the library's static scratch array: no workspace, no allocation."""
+    _check(lib().s2attn_bwd_ex_static(ctypes.byref(p), _stream(stream)))
 
 
 def s2attn_bwd_ex_marked(p: S2AttnParams, events, stream=None) -> None:

@@ -331,6 +331,49 @@ static int run_bwd(const s2attn_params* p, void* stream, void* const* events) {
 
 int s2attn_bwd_ex(const s2attn_params* p, void* stream) { return run_bwd(p, stream, nullptr); }
 
+// ---- backward without a caller workspace: the row terms (and, for a kv head that serves both
+// head classes, the fp32 partial sums) live in a device array that is part of the library's
+// code object.  Every GPU the library runs on holds its own copy at its own address, so the
+// address is looked up once per device, with that device current, and cached.
+namespace {
+static __device__ __align__(256) unsigned char scratch[S2ATTN_STATIC_SCRATCH_BYTES];
+std::atomic<void*> scratch_ptr[64];
+
+int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return S2ATTN_ERR_DEVICE;
+  void* ptr = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return S2ATTN_ERR_DEVICE;
+    scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return S2ATTN_OK;
+}
+}  // namespace
+
+int s2attn_bwd_ex_static(const s2attn_params* p, void* stream) {
+  if (!p) return S2ATTN_ERR_NULL;
+  s2attn_params local = *p;
+  local.bwd_algo = S2ATTN_BWD_RECOMPUTE;   // the stored-dS backward needs gigabytes of workspace
+  // size check first: pure host arithmetic, nothing is looked up or launched for a problem
+  // that does not fit
+  const size_t need = s2attn_bwd_workspace_bytes_ex(&local);
+  if (need > S2ATTN_STATIC_SCRATCH_BYTES) return S2ATTN_ERR_SCRATCH;
+  // the remaining argument errors do not depend on the workspace address
+  local.workspace = reinterpret_cast<void*>(static_cast<uintptr_t>(kAlign));
+  local.workspace_bytes = S2ATTN_STATIC_SCRATCH_BYTES;
+  int rc = check_common(&local, 1);
+  if (rc != S2ATTN_OK) return rc;
+  rc = check_device();
+  if (rc != S2ATTN_OK) return rc;
+  void* ptr = nullptr;
+  rc = static_scratch(&ptr);
+  if (rc != S2ATTN_OK) return rc;
+  local.workspace = ptr;
+  return run_bwd(&local, stream, nullptr);
+}
+
 int s2attn_bwd_ex_marked(const s2attn_params* p, void* stream, void* const* events) {
   return run_bwd(p, stream, events);
 }
@@ -385,6 +428,7 @@ const char* s2attn_strerror(int code) {
     case S2ATTN_ERR_TOO_LARGE: return "problem too large for the launch grid or index arithmetic";
     case S2ATTN_ERR_STRIDE: return "a stride is negative, misaligned or smaller than the extent it spans";
     case S2ATTN_ERR_ALGO: return "S2ATTN_BWD_STORED_DS needs bf16, G a multiple of 128, shift (and a Variant 2 split) of 64 (128), and no kv head serving both head classes";
+    case S2ATTN_ERR_SCRATCH: return "the backward needs more scratch than the library's static 16 MiB: call s2attn_bwd_ex with a workspace";
     default: return "unknown s2attn error code";
   }
 }

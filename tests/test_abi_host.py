@@ -208,3 +208,12 @@ def test_missing_library_is_an_error(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         binding.lib()
+
+
+def test_static_scratch_backward_refuses_large_problems_on_the_host():
+    """s2attn_bwd_ex_static checks the size before it looks at any pointer or at the GPU."""
+    p = params(B=1, N=131072, H=32, Hkv=32, D=128, G=8192)     # 4 Mi rows: 32 MiB of row terms
+    assert binding.lib().s2attn_bwd_ex_static(ctypes.byref(p), None) == -14
+    assert "static" in binding.strerror(-14)
+    p = params(B=1, N=16384, H=4, Hkv=1, D=128, G=1024)        # MQA: 32 MiB of partial sums
+    assert binding.lib().s2attn_bwd_ex_static(ctypes.byref(p), None) == -14
