@@ -143,7 +143,7 @@ int check_common(const s2attn_params* p, int backward) {
   if (p->dtype == S2ATTN_F32) {
     if (p->D != 64 && p->D != 128) return S2ATTN_ERR_HEADDIM;
   } else {
-    if (p->D != 128) return S2ATTN_ERR_HEADDIM;
+    if (p->D != 64 && p->D != 128) return S2ATTN_ERR_HEADDIM;
   }
   // grid z carries batch * heads (* 2 classes); element offsets are 64-bit
   if ((long long)p->B * p->H * 2 > 65535 || (long long)p->N / p->G > 65535) return S2ATTN_ERR_TOO_LARGE;
@@ -231,8 +231,9 @@ s2::KArgs make_kargs(const s2attn_params* p) {
   a.shifted_from = shifted_from(p, a.shift);
   a.split = (p->wrap_variant == S2ATTN_WRAP_SPLIT && a.shift > 0) ? p->G - a.shift : p->G;
   a.mixed = kv_heads_mixed(p->H, p->Hkv, a.shifted_from) ? 1 : 0;
-  a.ragged = (p->dtype == S2ATTN_BF16 &&
-              (p->G % 128 != 0 || a.shift % 64 != 0 || (a.split < p->G && a.split % 128 != 0))) ? 1 : 0;
+  // the kernels built for partial tiles also take rows narrower than the 128-element tile (D = 64)
+  a.ragged = (p->dtype == S2ATTN_BF16 && (p->D != 128 || p->G % 128 != 0 || a.shift % 64 != 0 ||
+                                          (a.split < p->G && a.split % 128 != 0))) ? 1 : 0;
   a.c_begin = 0;
   a.c_count = p->Hkv;
   a.scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->D);
@@ -420,7 +421,7 @@ const char* s2attn_strerror(int code) {
     case S2ATTN_ERR_DIM: return "B, N, H, Hkv, D and G must be positive";
     case S2ATTN_ERR_GROUP: return "need N % G == 0, G even and 0 <= shift < G";
     case S2ATTN_ERR_HEADS: return "need H even and H % Hkv == 0";
-    case S2ATTN_ERR_HEADDIM: return "unsupported head dimension (fp32: 64 or 128; bf16: 128)";
+    case S2ATTN_ERR_HEADDIM: return "unsupported head dimension (64 or 128)";
     case S2ATTN_ERR_WORKSPACE: return "backward workspace missing or smaller than s2attn_bwd_workspace_bytes";
     case S2ATTN_ERR_DTYPE: return "unknown dtype, shift rule or wrap variant";
     case S2ATTN_ERR_DEVICE: return "current device is not gfx950 (MI355X)";

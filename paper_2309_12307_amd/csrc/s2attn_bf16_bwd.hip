@@ -251,7 +251,10 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
     const bf16x8* ksrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.k) + row_off(a.sk, b, tok, c));
     const bf16x8* vsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.v) + row_off(a.sv, b, tok, c));
 #pragma unroll
-    for (int st = 0; st < 8; ++st) { kf[st] = ksrc[2 * st + g32]; vf[st] = -vsrc[2 * st + g32]; }
+    for (int st = 0; st < 8; ++st) {
+      kf[st] = row_frag<RAGGED>(ksrc, 2 * st + g32, a.D);
+      vf[st] = -row_frag<RAGGED>(vsrc, 2 * st + g32, a.D);
+    }
   }
 
   // staging: wave w, pass p fills tile rows 16p + 4w .. +3 (1 KB); in the aligned case
@@ -290,8 +293,8 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const int tok = run_token(a, run, q0 + 64 * hf + 16 * p + st_row, s);
-          dma16(qp + row_off(a.sq, b, tok, h) * 2 + st_chunk, qs + (64 * hf + 16 * p) * kRowBytes);
-          dma16(dop + row_off(a.so, b, tok, h) * 2 + st_chunk,
+          dma16(row_chunk<true>(qp + row_off(a.sq, b, tok, h) * 2, st_chunk, a.D), qs + (64 * hf + 16 * p) * kRowBytes);
+          dma16(row_chunk<true>(dop + row_off(a.so, b, tok, h) * 2, st_chunk, a.D),
                 qs + (64 * hf + 16 * p) * kRowBytes + kQTileBytes);
         }
         if (w == hf) {
@@ -366,17 +369,18 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
   // ---- store dK^T, dV^T blocks (keys lane-indexed) at un-rolled token rows
   if (a.dkv_partial) {
     // kv head shared by both classes: fp32 partial of this class, summed by the combine pass
-    const size_t kv_elems = (size_t)a.B * a.N * a.Hkv * 128;
+    const size_t kv_elems = (size_t)a.B * a.N * a.Hkv * a.D;
     float* dk_out = a.dkv_partial + (size_t)cls * kv_elems;
     float* dv_out = a.dkv_partial + (size_t)(2 + cls) * kv_elems;
     if (key >= run.len) return;   // padding key of a partial tile
     const int tok = token_of(run.p0 + key, s, a.N);
-    const size_t base = ((size_t)((size_t)b * a.N + tok) * a.Hkv + c) * 128;   // partials are contiguous
+    const size_t base = ((size_t)((size_t)b * a.N + tok) * a.Hkv + c) * a.D;   // partials are contiguous
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int vv = 0; vv < 4; ++vv) {
         const int d = 32 * db + 8 * vv + 4 * g32;
+        if (d >= a.D) continue;   // head dimension 64: the upper half of the tile is padding
         *reinterpret_cast<float4*>(dk_out + base + d) =
             make_float4(dk_acc[db][4 * vv] * a.scale, dk_acc[db][4 * vv + 1] * a.scale,
                         dk_acc[db][4 * vv + 2] * a.scale, dk_acc[db][4 * vv + 3] * a.scale);
@@ -395,7 +399,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
-    if (kw0 + row >= run.len) continue;   // padding key of a partial tile
+    if (kw0 + row >= run.len || ch * 8 >= a.D) continue;   // padding key of a partial tile, padding of a narrow row
     const int tok = token_of(run.p0 + kw0 + row, s, a.N);
     *reinterpret_cast<uint4*>(dkp + row_off(a.sdk, b, tok, c) + ch * 8) =
         *reinterpret_cast<const uint4*>(rk + tile_off(row, ch));
@@ -541,7 +545,10 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
     const bf16x8* qsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.q) + row_off(a.sq, b, tok, h));
     const bf16x8* dsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.dout) + row_off(a.so, b, tok, h));
 #pragma unroll
-    for (int st = 0; st < 8; ++st) { qf[st] = qsrc[2 * st + g32]; dof[st] = dsrc[2 * st + g32]; }
+    for (int st = 0; st < 8; ++st) {
+      qf[st] = row_frag<RAGGED>(qsrc, 2 * st + g32, a.D);
+      dof[st] = row_frag<RAGGED>(dsrc, 2 * st + g32, a.D);
+    }
     const size_t ro = ((size_t)b * a.H + h) * a.N + tok;
     lse2 = a.lse2[ro];
     delta = a.delta[ro];
@@ -570,8 +577,8 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const int tok = run_token(a, run, jt * BN + 16 * p + st_row, s);
-        dma16(kp + row_off(a.sk, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes);
-        dma16(vp + row_off(a.sv, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes + kTileBytes);
+        dma16(row_chunk<true>(kp + row_off(a.sk, b, tok, c) * 2, st_chunk, a.D), ks + 16 * p * kRowBytes);
+        dma16(row_chunk<true>(vp + row_off(a.sv, b, tok, c) * 2, st_chunk, a.D), ks + 16 * p * kRowBytes + kTileBytes);
       }
     }
   };
@@ -611,7 +618,7 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
-    if (qw0 + row >= run.len) continue;   // padding row of a partial tile
+    if (qw0 + row >= run.len || ch * 8 >= a.D) continue;   // padding row of a partial tile, padding of a narrow row
     const int tok = token_of(run.p0 + qw0 + row, s, a.N);
     *reinterpret_cast<uint4*>(dqp + row_off(a.sdq, b, tok, h) + ch * 8) =
         *reinterpret_cast<const uint4*>(region + tile_off(row, ch));

@@ -24,7 +24,6 @@ namespace s2 {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 #define S2_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
 
@@ -84,6 +83,33 @@ __device__ __forceinline__ bf16x8 frag_tr(const char* tile, const LaneOffsets& o
   const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
       S2_LDS(bf16x4, tile + o.tr[cb][1] + KROW0 * kRowBytes));
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Rows narrower than the 128-element tile (head dimension 64): the kernels built for partial
+// tiles read the chunks past the end of a row as zeros from this line, so a D = 64 problem
+// runs as a D = 128 problem whose upper 64 dimensions are zero (the products over them add
+// nothing; the outputs' upper half is not stored).
+static __device__ __attribute__((aligned(256))) const unsigned char kZeroLine[256] = {};
+
+// Address of the 16 bytes at byte offset `off` of a row of D bf16 elements, or of zeros past its end.
+template <bool NARROW>
+__device__ __forceinline__ const char* row_chunk(const char* row, int off, int D) {
+  if constexpr (NARROW) return off < 2 * D ? row + off : reinterpret_cast<const char*>(kZeroLine);
+  return row + off;
+}
+
+// 16-byte chunk c of a row of D bf16 elements as an operand fragment, zeros past its end.
+template <bool NARROW>
+__device__ __forceinline__ bf16x8 row_frag(const bf16x8* row, int c, int D) {
+  if constexpr (NARROW) {
+    if (8 * c >= D) {
+      bf16x8 z;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.f;
+      return z;
+    }
+  }
+  return row[c];
 }
 
 // Direct global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane i of

@@ -153,7 +153,7 @@ __device__ __forceinline__ void fwd_epilogue(const KArgs& a, FwdState& st, char*
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
     const uint4 val = *reinterpret_cast<const uint4*>(Os + tile_off(row, ch));
-    if (qw0 + row < run.len) {   // rows past the end of the run are padding of a partial tile
+    if (qw0 + row < run.len && ch * 8 < a.D) {   // rows past the end of the run are padding of a partial tile
       const int tok = token_of(run.p0 + qw0 + row, s, a.N);
       *reinterpret_cast<uint4*>(op + row_off(a.so, b, tok, h) + ch * 8) = val;
     }
@@ -224,7 +224,7 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
     const int tok = run_token(a, run, qrow, s);
     const bf16x8* src = reinterpret_cast<const bf16x8*>(qp + row_off(a.sq, b, tok, h));
 #pragma unroll
-    for (int st = 0; st < 8; ++st) qf[st] = src[2 * st + g32];
+    for (int st = 0; st < 8; ++st) qf[st] = row_frag<RAGGED>(src, 2 * st + g32, a.D);
   }
 
   // ---- K/V staging, global -> LDS: wave w, pass p fills tile rows 16p + 4w .. +3
@@ -253,8 +253,8 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const int tok = run_token(a, run, jt * BN + 16 * p + st_row, s);
-        dma16(kp + row_off(a.sk, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes);
-        dma16(vp + row_off(a.sv, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes + kTileBytes);
+        dma16(row_chunk<true>(kp + row_off(a.sk, b, tok, c) * 2, st_chunk, a.D), ks + 16 * p * kRowBytes);
+        dma16(row_chunk<true>(vp + row_off(a.sv, b, tok, c) * 2, st_chunk, a.D), ks + 16 * p * kRowBytes + kTileBytes);
       }
     }
   };

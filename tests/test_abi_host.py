@@ -87,7 +87,7 @@ def test_validator_accepts_benchmark_shapes():
     (dict(H=3, Hkv=3), -5),
     (dict(H=4, Hkv=3), -5),
     (dict(D=96), -6),
-    (dict(D=64), -6),                         # bf16 supports D = 128 only
+    (dict(D=256), -6),
     (dict(workspace_bytes=16), -8),
     (dict(workspace=0), -8),
     (dict(dtype=5), -9),
@@ -111,6 +111,7 @@ def test_validator_codes(kw, code):
     dict(G=25000, N=100000),            # the paper's 100k-token setting (Section 4.2), G = N / 4
     dict(shift=2),
     dict(wrap_variant=2),               # aligned Variant 2
+    dict(D=64),                           # head dimension 64 in bf16
     dict(G=200, N=1000, wrap_variant=2),  # Variant 2 with a partial last tile
     dict(shift=100, wrap_variant=2),      # Variant 2 split inside a tile
     dict(G=384, N=1536, wrap_variant=2),  # split at 192: a multiple of 64 but not of the 128-key tile
@@ -194,6 +195,7 @@ def test_workspace_size():
     (dict(bwd_algo=2, shift=32), -15),
     (dict(bwd_algo=2, H=2, Hkv=1), -15),                       # the kv head serves both head classes
     (dict(bwd_algo=2, dtype=1, D=64), -15),
+    (dict(bwd_algo=2, D=64), -15),                             # bf16 with head dimension 64
     (dict(bwd_algo=2, G=384, N=1536, wrap_variant=2), -15),    # Variant 2 split at 192
     (dict(bwd_algo=2, wrap_variant=2), 0),
     (dict(bwd_algo=2, workspace_bytes=2 * 4 * 1024 * 4), -8),  # row terms only: no room for one kv head's dS

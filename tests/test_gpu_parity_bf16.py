@@ -101,6 +101,45 @@ def test_stored_ds_backward_with_variant2_and_custom_shift():
         compare(out, ref)
 
 
+# Head dimension 64 (runs on the kernels built for partial tiles, with the upper half of the
+# 128-element tile rows read as zeros).
+D64_SHAPES = [
+    (1, 512, 2, 2, 64, 128),       # aligned group
+    (2, 1024, 4, 4, 64, 256),      # batch 2
+    (1, 2048, 8, 2, 64, 1024),     # GQA, 4 query heads per kv head
+    (1, 768, 2, 1, 64, 256),       # MQA: the kv head serves both classes (fp32 partial sums)
+    (1, 1536, 6, 3, 64, 512),      # odd Hkv
+    (1, 1000, 4, 2, 64, 500),      # partial tiles
+    (1, 390, 2, 2, 64, 130),
+    (1, 24, 2, 1, 64, 6),
+]
+
+
+@pytest.mark.parametrize("shape", D64_SHAPES)
+def test_head_dimension_64(shape):
+    from gpu_util import run_hip
+    B, N, H, Hkv, D, G = shape
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=64 + sum(shape), dtype="bf16")
+    out = run_hip(inp, G, "bf16")
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G)
+    compare(out, ref)
+
+
+def test_head_dimension_64_options():
+    """Variant 2, a custom shift with the all-heads rule, packed views and the static-scratch
+    backward at D = 64."""
+    from gpu_util import run_hip, run_hip_packed
+    from paper_2309_12307_amd import binding
+    B, N, H, Hkv, D, G = 1, 1536, 4, 2, 64, 384
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=640, dtype="bf16")
+    out = run_hip(inp, G, "bf16", wrap_variant=binding.WRAP_SPLIT)
+    compare(out, orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, variant2=True))
+    out = run_hip(inp, G, "bf16", shift=100, shift_rule=binding.SHIFT_ALL)
+    compare(out, orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, shift=100, shift_heads="all"))
+    out = run_hip_packed(inp, G, "bf16")
+    compare(out, orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G))
+
+
 def test_full_causal_attention_mode():
     from gpu_util import run_hip
     from paper_2309_12307_amd import binding
