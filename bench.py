@@ -24,12 +24,39 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script,
-# scaled by a 1 GiB copy probe (profiles/s2attn_fwd_bwd_C3_rocprofv3.md), keyed by workload
-# then kernel.  Not measurable from inside the process; null for workloads not profiled.
-MEASURED_TRAFFIC = {
-    "C3": {"fwd": 1.838e9, "bwd_dkdv": 2.472e9, "bwd_dq": 2.569e9},
-}
+CSRC = os.path.join(ROOT, "paper_2309_12307_amd", "csrc")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def source_hash() -> str:
+    """sha256 over the kernel sources, to tie profiled figures to the code they were measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".hip", ".h")) and name != "s2attn_probes.hip":
+            h.update(name.encode())
+            h.update(open(os.path.join(CSRC, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str, algo: str, kernel: str):
+    """HBM bytes per launch of `kernel` from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+    recorded in profiles/hbm_traffic.txt (not measurable from inside the process).  None when
+    the workload was not profiled or the kernel sources have changed since."""
+    if not os.path.exists(TRAFFIC_FILE):
+        return None
+    recorded_hash, table = None, {}
+    for line in open(TRAFFIC_FILE):
+        f = line.split()
+        if not f or f[0].startswith("#"):
+            continue
+        if f[0] == "source_sha256":
+            recorded_hash = f[1]
+        elif len(f) == 4:
+            table[(f[0], f[1], f[2])] = float(f[3])
+    if recorded_hash != source_hash():
+        return None
+    return table.get((workload, algo, kernel))
 
 
 class HipEvents:
@@ -95,6 +122,39 @@ def cpu_baseline(cfg, inp, budget_s=15.0):
     }
 
 
+def run_probes():
+    path = os.path.join(ROOT, "paper_2309_12307_amd", "libs2attn_probes.so")
+    if not os.path.exists(path):
+        raise SystemExit(f"{path} not found: build it with `python -m paper_2309_12307_amd.build`")
+    L = ctypes.CDLL(path)
+    dbl = ctypes.c_double
+    out = {"probe": "MI355X bf16 32x32x16 MFMA rate against operand data, L2 fp32 atomic rate",
+           "unit": "TFLOP/s", "mfma_registers": {}, "mfma_lds_operand": []}
+
+    def call(f, *a):
+        v = dbl()
+        rc = f(*a, ctypes.byref(v))
+        if rc != 0:
+            raise RuntimeError(f"probe failed with hipError {rc}")
+        return v.value
+
+    for mode, name in ((0, "ones"), (1, "randn")):
+        out["mfma_registers"][name] = round(call(L.s2probe_mfma_registers, mode), 1)
+    work = {0: "none", 1: "3 fma + 1 exp2 per MFMA", 2: "4 fma + 2 exp2 per MFMA"}
+    for waves in (2, 1):
+        for tr in (0, 1):
+            for vw in (0, 1, 2):
+                for reuse in (1, 2):
+                    row = {"waves_per_simd": waves, "fragments": "transposed 2 x b64" if tr else "row-major b128",
+                           "vector_work": work[vw], "mfma_per_lds_fragment": reuse}
+                    for mode, name in ((0, "ones"), (1, "randn")):
+                        row[name] = round(call(L.s2probe_mfma_lds, tr, vw, waves, reuse, mode), 1)
+                    out["mfma_lds_operand"].append(row)
+                    print(row, file=sys.stderr, flush=True)
+    out["l2_fp32_atomic_add_TB_per_s"] = round(call(L.s2probe_atomic_add), 3)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,7 +174,18 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known HBM traffic to scale FETCH_SIZE/WRITE_SIZE by")
+    ap.add_argument("--probes", action="store_true",
+                    help="instead of the benchmark, run the hardware probes of libs2attn_probes.so (bf16 MFMA rate "
+                         "against operand data, with register and LDS operands and softmax-like vector work; L2 "
+                         "fp32 atomic-add rate) and print them as one JSON line")
+    ap.add_argument("--source-hash", action="store_true", help="print the hash of the kernel sources and exit")
     args = ap.parse_args()
+    if args.source_hash:
+        print(source_hash())
+        return
+    if args.probes:
+        run_probes()
+        return
     if args.gpus != 1:
         print("bench.py measures the single-GPU S2-Attn kernels only: this build has no multi-GPU path "
               "(--gpus must be 1)", file=sys.stderr)
@@ -210,7 +281,7 @@ def main():
     kernels = {n: {"ms": dur[n], "algorithmic_tflops": alg[n] / dur[n] / 1e9 if n in alg else None} for n in names}
     dom = max(alg, key=lambda n: dur[n])
     achieved = alg[dom] / dur[dom] / 1e9
-    traffic = MEASURED_TRAFFIC.get(cfg.name, {}).get(dom)
+    traffic = measured_traffic(cfg.name, "stored" if args.bwd_algo == "stored" else "recompute", dom)
 
     value = flops_total / (ms_per_step * 1e-3) / 1e12
     out = {

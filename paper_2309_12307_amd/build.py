@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libs2attn.so")
+PROBES_LIB = os.path.join(HERE, "libs2attn_probes.so")
 SOURCES = ["s2attn_api.hip", "s2attn_prepost.hip", "s2attn_f32.hip", "s2attn_bf16_fwd.hip", "s2attn_bf16_bwd.hip",
            "s2attn_bf16_dkdv_split.hip", "s2attn_bf16_dq_spill.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -45,7 +46,22 @@ def build(verbose: bool = True, extra_flags=(), out_path: str | None = None) -> 
     subprocess.run(link, check=True)
     if verbose:
         sys.stderr.write(f"[build] wrote {lib}\n")
+    if out_path is None:
+        build_probes(hipcc, verbose)
     return lib
+
+
+def build_probes(hipcc: str, verbose: bool) -> str:
+    """libs2attn_probes.so: the hardware probes of bench.py --probes (MFMA rate against operand
+    data, L2 atomic rate).  Separate from the attention library, which does not depend on it."""
+    cmd = [hipcc, *FLAGS, "-munsafe-fp-atomics", "-shared", "-o", PROBES_LIB, os.path.join(CSRC, "s2attn_probes.hip")]
+    p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if p.returncode != 0:
+        sys.stderr.write(p.stdout)
+        raise RuntimeError("hipcc failed on s2attn_probes.hip")
+    if verbose:
+        sys.stderr.write(f"[build] wrote {PROBES_LIB}\n")
+    return PROBES_LIB
 
 
 if __name__ == "__main__":
