@@ -81,3 +81,52 @@ def test_static_scratch_backward_refuses_what_does_not_fit():
     with pytest.raises(binding.S2AttnError) as e:
         binding.s2attn_bwd_ex_static(p)
     assert e.value.code == -14
+
+
+def test_forward_and_static_scratch_backward_replay_from_a_hip_graph():
+    """The use the entry point is for: forward + backward captured once into a HIP graph (no
+    allocation, no host synchronisation inside the calls) and replayed on new inputs, with
+    eager work and synchronisations between the replays; every replay must equal the eager
+    result bit for bit."""
+    import torch
+    from gpu_util import to_dev
+    from paper_2309_12307_amd import binding
+    B, N, H, Hkv, D, G = 1, 2048, 4, 2, 128, 512
+    q, k, v, do = (torch.zeros((B, N, h, D), dtype=torch.bfloat16, device="cuda") for h in (H, Hkv, Hkv, H))
+    o, dq = torch.zeros_like(q), torch.zeros_like(q)
+    dk, dv = torch.zeros_like(k), torch.zeros_like(v)
+    lse = torch.zeros((B, H, N), dtype=torch.float32, device="cuda")
+    p_fwd = binding.make_params(q, k, v, o, lse, G)
+    p_bwd = binding.make_params(q, k, v, o, lse, G, dout=do, dq=dq, dk=dk, dv=dv)
+
+    def load(seed):
+        inp = inputs.make_inputs(B, N, H, Hkv, D, seed=seed, dtype="bf16")
+        for t, name in ((q, "q"), (k, "k"), (v, "v"), (do, "do")):
+            t.copy_(to_dev(inp[name], inp[name + "_bits"]))
+
+    def run():
+        binding.s2attn_fwd_ex(p_fwd)
+        binding.s2attn_bwd_ex_static(p_bwd)
+
+    load(720)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                # warm-up outside the capture (device check, scratch address)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for seed in (721, 722, 723):
+        load(seed)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (o, lse, dq, dk, dv)]
+        for t in (o, lse, dq, dk, dv):
+            t.fill_(float("nan"))
+        run()                                # eager, same inputs
+        torch.cuda.synchronize()
+        for name, a, b in zip(("o", "lse", "dq", "dk", "dv"), got, (o, lse, dq, dk, dv)):
+            assert torch.isfinite(a.float()).all(), (seed, name)
+            assert torch.equal(a, b), (seed, name)
