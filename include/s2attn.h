@@ -52,8 +52,7 @@ enum {
   S2ATTN_ERR_DIM = -3,         /* B, N, H, Hkv, D or G is not positive */
   S2ATTN_ERR_GROUP = -4,       /* N % G != 0, or G odd, or shift outside [0, G) */
   S2ATTN_ERR_HEADS = -5,       /* H odd (half of the heads shift), H % Hkv != 0, or inconsistent head sharding */
-  S2ATTN_ERR_HEADDIM = -6,     /* D not supported: D must be 64 or 128 (bf16 kernels are built for 128; 64 runs on
-                                  them with the upper half of every row read as zeros, at half their efficiency) */
+  S2ATTN_ERR_HEADDIM = -6,     /* D not supported: D must be 64 or 128 */
   /* -7 is unused (it was a tile-alignment error that no longer exists) */
   S2ATTN_ERR_WORKSPACE = -8,   /* backward workspace missing or too small */
   S2ATTN_ERR_DTYPE = -9,       /* unknown dtype / rule / variant value */

@@ -63,22 +63,24 @@ __device__ __forceinline__ void mma_sc(const bf16x8 (&buf)[8], DkdvBlock& blk, c
     blk.dp = mfma32(buf[4 + i], vf[4 * H + i], blk.dp);
   }
 }
-// accumulate phase (block MB, queries 16T..16T+15 of it): dV^T += dO^T P, dK^T += Q^T dS
-template <int MB, int T>
+// accumulate phase (block MB, queries 16T..16T+15 of it): dV^T += dO^T P, dK^T += Q^T dS.
+// DH: head dimension the products run over (128, or 64 when the upper half of every tile row is
+// zero padding).
+template <int MB, int T, int DH = 128>
 __device__ __forceinline__ void load_acc(bf16x8 (&buf)[8], const DkdvTile& t) {
 #pragma unroll
-  for (int db = 0; db < 4; ++db) {
+  for (int db = 0; db < DH / 32; ++db) {
     buf[db] = frag_tr<32 * MB + 16 * T>(t.dOs, t.lo, db);
     buf[4 + db] = frag_tr<32 * MB + 16 * T>(t.Qs, t.lo, db);
   }
 }
-template <int T>
+template <int T, int DH = 128>
 __device__ __forceinline__ void mma_acc(const bf16x8 (&buf)[8], const bf16x4 (&pq)[4], const bf16x4 (&dsq)[4],
                                         f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4]) {
   const bf16x8 pf = __builtin_shufflevector(pq[2 * T], pq[2 * T + 1], 0, 1, 2, 3, 4, 5, 6, 7);
   const bf16x8 dsf = __builtin_shufflevector(dsq[2 * T], dsq[2 * T + 1], 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-  for (int db = 0; db < 4; ++db) {
+  for (int db = 0; db < DH / 32; ++db) {
     dv_acc[db] = mfma32(buf[db], pf, dv_acc[db]);
     dk_acc[db] = mfma32(buf[4 + db], dsf, dk_acc[db]);
   }
@@ -165,8 +167,8 @@ __device__ __forceinline__ void dkdv_interior_tile(const DkdvTile& t, const bf16
 #undef S2_PHASE_END
 }
 
-// One 32-query block without pipelining (diagonal tiles).
-template <bool MASK>
+// One 32-query block without pipelining (diagonal tiles; every tile when the head dimension is 64).
+template <bool MASK, int DH = 128>
 __device__ __forceinline__ void dkdv_block(const DkdvTile& t, int mb, int q_first, int key, const bf16x8 (&kf)[8],
                                            const bf16x8 (&vf)[8], f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4],
                                            int q_lim = INT32_MAX) {
@@ -179,21 +181,24 @@ __device__ __forceinline__ void dkdv_block(const DkdvTile& t, int mb, int q_firs
   DkdvBlock blk;
   bf16x4 pq[4], dsq[4];
   blk.s = zero16(); init_dp<0>(blk, tt);
-  load_sc<0, 0>(fa, tt); load_sc<0, 1>(fb, tt);
-  mma_sc<0>(fa, blk, kf, vf); mma_sc<1>(fb, blk, kf, vf);
-  load_acc<0, 0>(fa, tt); load_acc<0, 1>(fb, tt);
+  load_sc<0, 0>(fa, tt);
+  if constexpr (DH == 128) load_sc<0, 1>(fb, tt);
+  mma_sc<0>(fa, blk, kf, vf);
+  if constexpr (DH == 128) mma_sc<1>(fb, blk, kf, vf);
+  load_acc<0, 0, DH>(fa, tt); load_acc<0, 1, DH>(fb, tt);
   sm_quarter<0, 0, MASK>(blk, tt, pq[0], dsq[0], q_first, key, q_lim);
   sm_quarter<0, 1, MASK>(blk, tt, pq[1], dsq[1], q_first, key, q_lim);
   sm_quarter<0, 2, MASK>(blk, tt, pq[2], dsq[2], q_first, key, q_lim);
   sm_quarter<0, 3, MASK>(blk, tt, pq[3], dsq[3], q_first, key, q_lim);
-  mma_acc<0>(fa, pq, dsq, dk_acc, dv_acc);
-  mma_acc<1>(fb, pq, dsq, dk_acc, dv_acc);
+  mma_acc<0, DH>(fa, pq, dsq, dk_acc, dv_acc);
+  mma_acc<1, DH>(fb, pq, dsq, dk_acc, dv_acc);
 }
 
 // RAGGED: G is not a multiple of 128 or the shift not of 64 -- tiles may be partial and
 // the wrap point may fall inside one, so every staged row finds its own token and the
 // padding rows of the last tile are masked.  The aligned instantiation carries none of it.
-template <bool RAGGED>
+// DH = 64 (only with RAGGED): the head dimension is 64 and the products skip the zero half.
+template <bool RAGGED, int DH = 128>
 __global__ void __launch_bounds__(256, 1)
 bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
   __shared__ __attribute__((aligned(1024))) char smem[4 * kQTileBytes];            // [stage][Q,dO]
@@ -251,10 +256,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
     const bf16x8* ksrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.k) + row_off(a.sk, b, tok, c));
     const bf16x8* vsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.v) + row_off(a.sv, b, tok, c));
 #pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      kf[st] = row_frag<RAGGED>(ksrc, 2 * st + g32, a.D);
-      vf[st] = -row_frag<RAGGED>(vsrc, 2 * st + g32, a.D);
-    }
+    for (int st = 0; st < DH / 16; ++st) { kf[st] = ksrc[2 * st + g32]; vf[st] = -vsrc[2 * st + g32]; }
   }
 
   // staging: wave w, pass p fills tile rows 16p + 4w .. +3 (1 KB); in the aligned case
@@ -293,8 +295,9 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const int tok = run_token(a, run, q0 + 64 * hf + 16 * p + st_row, s);
-          dma16(row_chunk<true>(qp + row_off(a.sq, b, tok, h) * 2, st_chunk, a.D), qs + (64 * hf + 16 * p) * kRowBytes);
-          dma16(row_chunk<true>(dop + row_off(a.so, b, tok, h) * 2, st_chunk, a.D),
+          if (DH == 64 && st_chunk >= 2 * DH) continue;   // a 64-wide row fills the first eight chunks only
+          dma16(qp + row_off(a.sq, b, tok, h) * 2 + st_chunk, qs + (64 * hf + 16 * p) * kRowBytes);
+          dma16(dop + row_off(a.so, b, tok, h) * 2 + st_chunk,
                 qs + (64 * hf + 16 * p) * kRowBytes + kQTileBytes);
         }
         if (w == hf) {
@@ -345,7 +348,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
       if constexpr (RAGGED) {
         // query rows >= G (padding of a partial tile) give P = 0; blocks before this wave's
         // keys are skipped
-        for (int mb = w; mb < 4; ++mb) dkdv_block<true>(t, mb, j0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, run.len);
+        for (int mb = w; mb < 4; ++mb) dkdv_block<true, DH>(t, mb, j0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, run.len);
       } else {
         // block mb < w is entirely before this wave's keys, block w is masked
         dkdv_block<true>(t, w, j0 + 32 * w, key, kf, vf, dk_acc, dv_acc);
@@ -355,12 +358,16 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
     }
     for (int it = 1; it < n_full; ++it, ++n) {
       const DkdvTile t = begin_tile(n, hh, it);
-      dkdv_interior_tile(t, kf, vf, dk_acc, dv_acc);
+      if constexpr (DH == 128) {
+        dkdv_interior_tile(t, kf, vf, dk_acc, dv_acc);
+      } else {
+        for (int mb = 0; mb < 4; ++mb) dkdv_block<false, DH>(t, mb, 0, key, kf, vf, dk_acc, dv_acc);
+      }
     }
     if (has_tail && nq > 1) {
       const DkdvTile t = begin_tile(n, hh, nq - 1);
       const int q0 = j0 + (nq - 1) * kQTileRows;
-      for (int mb = 0; mb < 4; ++mb) dkdv_block<true>(t, mb, q0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, run.len);
+      for (int mb = 0; mb < 4; ++mb) dkdv_block<true, DH>(t, mb, q0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, run.len);
       ++n;
     }
   }
@@ -497,7 +504,41 @@ __device__ __forceinline__ void dq_tile(f32x16 (&dq_acc)[4], const bf16x8 (&qf)[
 #undef S2_DQ_STEP
 }
 
-template <bool RAGGED>
+// Head dimension 64 (the upper half of every tile row is zero padding): the same three
+// products over d = 0 .. 63 only, one 32-key block after the other, without the step pipeline.
+template <int ROW0>
+__device__ __forceinline__ void dq_scores64(f32x16& sa, f32x16& pa, const bf16x8 (&qf)[8], const bf16x8 (&dof)[8],
+                                            const char* Ks, const char* Vs, const LaneOffsets& lo) {
+  bf16x8 kfr[4], vfr[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) { kfr[k] = frag_rm<ROW0>(Ks, lo, k); vfr[k] = frag_rm<ROW0>(Vs, lo, k); }
+#pragma unroll
+  for (int k = 0; k < 4; ++k) { sa = mfma32(kfr[k], qf[k], sa); pa = mfma32(vfr[k], dof[k], pa); }
+}
+template <int KROW0>
+__device__ __forceinline__ void dq_acc64(f32x16 (&dq_acc)[4], const char* Ks, const LaneOffsets& lo, bf16x8 dsf) {
+#pragma unroll
+  for (int db = 0; db < 2; ++db) dq_acc[db] = mfma32(frag_tr<KROW0>(Ks, lo, db), dsf, dq_acc[db]);
+}
+__device__ __forceinline__ void dq_tile64(f32x16 (&dq_acc)[4], const bf16x8 (&qf)[8], const bf16x8 (&dof)[8],
+                                          const char* Ks, const char* Vs, const LaneOffsets& lo, int j0,
+                                          int qrow, float c2, float lse2, float delta, int g32, bool masked) {
+  bf16x8 dsf[4];
+  f32x16 sa = zero16(), pa = zero16();
+  dq_scores64<0>(sa, pa, qf, dof, Ks, Vs, lo);
+  dq_ds<0>(sa, pa, dsf[0], dsf[1], j0, qrow, c2, lse2, delta, g32, masked);
+  sa = zero16();
+  pa = zero16();
+  dq_scores64<32>(sa, pa, qf, dof, Ks, Vs, lo);
+  dq_ds<32>(sa, pa, dsf[2], dsf[3], j0, qrow, c2, lse2, delta, g32, masked);
+  dq_acc64<0>(dq_acc, Ks, lo, dsf[0]);
+  dq_acc64<16>(dq_acc, Ks, lo, dsf[1]);
+  dq_acc64<32>(dq_acc, Ks, lo, dsf[2]);
+  dq_acc64<48>(dq_acc, Ks, lo, dsf[3]);
+}
+
+// DH = 64 (only with RAGGED): the head dimension is 64 and the products skip the zero half.
+template <bool RAGGED, int DH = 128>
 __global__ void __launch_bounds__(256, 2)
 bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   constexpr int BM = 128;
@@ -545,10 +586,7 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
     const bf16x8* qsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.q) + row_off(a.sq, b, tok, h));
     const bf16x8* dsrc = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(a.dout) + row_off(a.so, b, tok, h));
 #pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      qf[st] = row_frag<RAGGED>(qsrc, 2 * st + g32, a.D);
-      dof[st] = row_frag<RAGGED>(dsrc, 2 * st + g32, a.D);
-    }
+    for (int st = 0; st < DH / 16; ++st) { qf[st] = qsrc[2 * st + g32]; dof[st] = dsrc[2 * st + g32]; }
     const size_t ro = ((size_t)b * a.H + h) * a.N + tok;
     lse2 = a.lse2[ro];
     delta = a.delta[ro];
@@ -577,8 +615,10 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const int tok = run_token(a, run, jt * BN + 16 * p + st_row, s);
-        dma16(row_chunk<true>(kp + row_off(a.sk, b, tok, c) * 2, st_chunk, a.D), ks + 16 * p * kRowBytes);
-        dma16(row_chunk<true>(vp + row_off(a.sv, b, tok, c) * 2, st_chunk, a.D), ks + 16 * p * kRowBytes + kTileBytes);
+        if (DH == 128 || st_chunk < 2 * DH) {   // a 64-wide row fills the first eight chunks only
+          dma16(kp + row_off(a.sk, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes);
+          dma16(vp + row_off(a.sv, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes + kTileBytes);
+        }
       }
     }
   };
@@ -603,7 +643,10 @@ bwd_dq_bf16_kernel(KArgs a, int T, int il, int n_rest) {
     const char* Ks = smem + STAGE * 2 * kTileBytes;
     const char* Vs = Ks + kTileBytes;
     if (j0 > qw0 + 31 || j0 + BN - 1 < lo_w) return;   // wholly outside this wave's visible keys
-    dq_tile(dq_acc, qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32, j0 + BN - 1 > qw0);
+    if constexpr (DH == 128)
+      dq_tile(dq_acc, qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32, j0 + BN - 1 > qw0);
+    else
+      dq_tile64(dq_acc, qf, dof, Ks, Vs, lo, j0, qrow, c2, lse2, delta, g32, j0 + BN - 1 > qw0);
   };
   for (int n = 0; n < n_tiles; n += 2) {
     body(std::integral_constant<int, 0>{}, n);
@@ -635,7 +678,9 @@ int launch_bwd_dkdv_bf16(const KArgs& a, hipStream_t st) {
   const int n_rest = a.B * a.Hkv * ncls * NG;
   const int il = interleave_for(T, 32);   // 32 CUs per XCD, one workgroup each
   const int blocks = 8 * T * pad_to((n_rest + 7) / 8, il);
-  if (a.ragged)
+  if (a.D == 64)
+    hipLaunchKernelGGL((bwd_dkdv_bf16_kernel<true, 64>), dim3(blocks), dim3(256), 0, st, a, ncls, T, il, n_rest);
+  else if (a.ragged)
     hipLaunchKernelGGL(bwd_dkdv_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, ncls, T, il, n_rest);
   else
     hipLaunchKernelGGL(bwd_dkdv_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, ncls, T, il, n_rest);
@@ -648,7 +693,9 @@ int launch_bwd_dq_bf16(const KArgs& a, hipStream_t st) {
   const int n_rest = a.B * a.Hkv * NG;
   const int il = interleave_for(T, 64);   // 32 CUs per XCD, two workgroups each
   const int blocks = 8 * T * pad_to(a.r * ((n_rest + 7) / 8), il);
-  if (a.ragged)
+  if (a.D == 64)
+    hipLaunchKernelGGL((bwd_dq_bf16_kernel<true, 64>), dim3(blocks), dim3(256), 0, st, a, T, il, n_rest);
+  else if (a.ragged)
     hipLaunchKernelGGL(bwd_dq_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, T, il, n_rest);
   else
     hipLaunchKernelGGL(bwd_dq_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, T, il, n_rest);

@@ -86,31 +86,10 @@ __device__ __forceinline__ bf16x8 frag_tr(const char* tile, const LaneOffsets& o
 }
 
 // Rows narrower than the 128-element tile (head dimension 64): the kernels built for partial
-// tiles read the chunks past the end of a row as zeros from this line, so a D = 64 problem
-// runs as a D = 128 problem whose upper 64 dimensions are zero (the products over them add
-// nothing; the outputs' upper half is not stored).
-static __device__ __attribute__((aligned(256))) const unsigned char kZeroLine[256] = {};
-
-// Address of the 16 bytes at byte offset `off` of a row of D bf16 elements, or of zeros past its end.
-template <bool NARROW>
-__device__ __forceinline__ const char* row_chunk(const char* row, int off, int D) {
-  if constexpr (NARROW) return off < 2 * D ? row + off : reinterpret_cast<const char*>(kZeroLine);
-  return row + off;
-}
-
-// 16-byte chunk c of a row of D bf16 elements as an operand fragment, zeros past its end.
-template <bool NARROW>
-__device__ __forceinline__ bf16x8 row_frag(const bf16x8* row, int c, int D) {
-  if constexpr (NARROW) {
-    if (8 * c >= D) {
-      bf16x8 z;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.f;
-      return z;
-    }
-  }
-  return row[c];
-}
+// tiles have a second instantiation (DH = 64) that stages only the first eight 16-byte chunks
+// of every tile row, loads only the first four register fragments of a row, runs its products
+// over d = 0 .. 63 and stores the first half of the output tiles; the upper half of the LDS
+// rows is never read.
 
 // Direct global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane i of
 // the wave fetches the 16 bytes at its own global address `g`, and they land at LDS byte

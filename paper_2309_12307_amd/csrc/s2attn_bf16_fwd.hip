@@ -31,18 +31,20 @@ struct FwdState {
   float l_run;    // this lane's part of the running row sum
 };
 
-// O^T += V^T P^T for the 16 keys starting at tile row KROW0.
-template <int KROW0>
+// O^T += V^T P^T for the 16 keys starting at tile row KROW0.  DH: head dimension the products
+// run over (128, or 64 when the upper half of every tile row is zero padding).
+template <int KROW0, int DH = 128>
 __device__ __forceinline__ void pv_step(FwdState& st, const char* Vs, const LaneOffsets& lo, bf16x8 pf) {
-  bf16x8 vf[4];
+  bf16x8 vf[DH / 32];
 #pragma unroll
-  for (int db = 0; db < 4; ++db) vf[db] = frag_tr<KROW0>(Vs, lo, db);
+  for (int db = 0; db < DH / 32; ++db) vf[db] = frag_tr<KROW0>(Vs, lo, db);
 #pragma unroll
-  for (int db = 0; db < 4; ++db) st.o_acc[db] = mfma32(vf[db], pf, st.o_acc[db]);
+  for (int db = 0; db < DH / 32; ++db) st.o_acc[db] = mfma32(vf[db], pf, st.o_acc[db]);
 }
 
 // S^T = K Q^T of one 64-key tile for one wave (32 queries): two 32-key blocks.
 // `masked` is wave-uniform: the tile touches the diagonal of this wave's rows.
+template <int DH = 128>
 __device__ __forceinline__ void fwd_scores(f32x16& s0, f32x16& s1, const bf16x8 (&qf)[8], const char* Ks,
                                            const LaneOffsets& lo, int j0, int qrow, int g32, bool masked) {
   s0 = zero16();
@@ -58,15 +60,17 @@ __device__ __forceinline__ void fwd_scores(f32x16& s0, f32x16& s1, const bf16x8 
     s0 = mfma32(ka[i], qf[i], s0);
     s1 = mfma32(kb[i], qf[i], s1);
   }
+  if constexpr (DH == 128) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    ka[i] = frag_rm<0>(Ks, lo, i + 4);
-    kb[i] = frag_rm<32>(Ks, lo, i + 4);
-  }
+    for (int i = 0; i < 4; ++i) {
+      ka[i] = frag_rm<0>(Ks, lo, i + 4);
+      kb[i] = frag_rm<32>(Ks, lo, i + 4);
+    }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    s0 = mfma32(ka[i], qf[i + 4], s0);
-    s1 = mfma32(kb[i], qf[i + 4], s1);
+    for (int i = 0; i < 4; ++i) {
+      s0 = mfma32(ka[i], qf[i + 4], s0);
+      s1 = mfma32(kb[i], qf[i + 4], s1);
+    }
   }
   if (masked) {
 #pragma unroll
@@ -116,20 +120,22 @@ __device__ __forceinline__ void fwd_softmax(FwdState& st, f32x16& s0, f32x16& s1
 }
 
 // O^T += V^T P^T for the whole 64-key tile.
+template <int DH = 128>
 __device__ __forceinline__ void fwd_pv(FwdState& st, const char* Vs, const LaneOffsets& lo, const bf16x8 (&pf)[4]) {
-  pv_step<0>(st, Vs, lo, pf[0]);
-  pv_step<16>(st, Vs, lo, pf[1]);
-  pv_step<32>(st, Vs, lo, pf[2]);
-  pv_step<48>(st, Vs, lo, pf[3]);
+  pv_step<0, DH>(st, Vs, lo, pf[0]);
+  pv_step<16, DH>(st, Vs, lo, pf[1]);
+  pv_step<32, DH>(st, Vs, lo, pf[2]);
+  pv_step<48, DH>(st, Vs, lo, pf[3]);
 }
 
+template <int DH = 128>
 __device__ __forceinline__ void fwd_tile(FwdState& st, const bf16x8 (&qf)[8], const char* Ks, const char* Vs,
                                          const LaneOffsets& lo, int j0, int qrow, float c2, int g32, bool masked) {
   f32x16 s0, s1;
   bf16x8 pf[4];
-  fwd_scores(s0, s1, qf, Ks, lo, j0, qrow, g32, masked);
+  fwd_scores<DH>(s0, s1, qf, Ks, lo, j0, qrow, g32, masked);
   fwd_softmax(st, s0, s1, c2, pf);
-  fwd_pv(st, Vs, lo, pf);
+  fwd_pv<DH>(st, Vs, lo, pf);
 }
 
 // Normalises a wave's 32 x 128 output block, transposes it through the wave's private
@@ -168,7 +174,8 @@ __device__ __forceinline__ void fwd_epilogue(const KArgs& a, FwdState& st, char*
 // tiles may be partial and the wrap point may fall inside one, so every staged row finds
 // its own token, and the two halves of a split wrap-around group run as causal runs of
 // their own (run_of_tile).
-template <bool RAGGED>
+// DH = 64 (only with RAGGED): the head dimension is 64 and the products skip the zero half.
+template <bool RAGGED, int DH = 128>
 __global__ void __launch_bounds__(256, 2)
 fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
   constexpr int BM = 128;
@@ -224,7 +231,7 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
     const int tok = run_token(a, run, qrow, s);
     const bf16x8* src = reinterpret_cast<const bf16x8*>(qp + row_off(a.sq, b, tok, h));
 #pragma unroll
-    for (int st = 0; st < 8; ++st) qf[st] = row_frag<RAGGED>(src, 2 * st + g32, a.D);
+    for (int st = 0; st < DH / 16; ++st) qf[st] = src[2 * st + g32];
   }
 
   // ---- K/V staging, global -> LDS: wave w, pass p fills tile rows 16p + 4w .. +3
@@ -253,8 +260,10 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const int tok = run_token(a, run, jt * BN + 16 * p + st_row, s);
-        dma16(row_chunk<true>(kp + row_off(a.sk, b, tok, c) * 2, st_chunk, a.D), ks + 16 * p * kRowBytes);
-        dma16(row_chunk<true>(vp + row_off(a.sv, b, tok, c) * 2, st_chunk, a.D), ks + 16 * p * kRowBytes + kTileBytes);
+        if (DH == 128 || st_chunk < 2 * DH) {   // a 64-wide row fills the first eight chunks only
+          dma16(kp + row_off(a.sk, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes);
+          dma16(vp + row_off(a.sv, b, tok, c) * 2 + st_chunk, ks + 16 * p * kRowBytes + kTileBytes);
+        }
       }
     }
   };
@@ -281,7 +290,7 @@ fwd_bf16_kernel(KArgs a, int T, int il, int n_rest) {
     // this wave's rows see keys [lo_w, row]: skip tiles wholly outside (beyond the
     // diagonal, or, under Variant 2, in the other block of the wrap group)
     if (j0 > qw0 + 31 || j0 + BN - 1 < lo_w) continue;
-    fwd_tile(st, qf, Ks, Vs, lo, j0, qrow, c2, g32, j0 + BN - 1 > qw0);
+    fwd_tile<DH>(st, qf, Ks, Vs, lo, j0, qrow, c2, g32, j0 + BN - 1 > qw0);
   }
   __syncthreads();
 
@@ -510,7 +519,9 @@ int launch_fwd_bf16(const KArgs& a, hipStream_t st) {
   const int n_rest = a.B * a.Hkv * (a.N / a.G);
   const int il = interleave_for(T, 64);   // 32 CUs per XCD, two workgroups each
   const int blocks = 8 * T * pad_to(a.r * ((n_rest + 7) / 8), il);
-  if (a.ragged)
+  if (a.D == 64)
+    hipLaunchKernelGGL((fwd_bf16_kernel<true, 64>), dim3(blocks), dim3(256), 0, st, a, T, il, n_rest);
+  else if (a.ragged)
     hipLaunchKernelGGL(fwd_bf16_kernel<true>, dim3(blocks), dim3(256), 0, st, a, T, il, n_rest);
   else
     hipLaunchKernelGGL(fwd_bf16_kernel<false>, dim3(blocks), dim3(256), 0, st, a, T, il, n_rest);
