@@ -204,6 +204,21 @@ def test_variant2_split_not_on_a_tile_boundary(shape, shift):
     compare(out, ref)
 
 
+def test_variant2_split_inside_a_workgroup_of_the_eight_wave_forward():
+    """G = 2304 = 9 x 256 runs the eight-wave forward kernel (256 query rows per workgroup);
+    the default shift 1152 puts the Variant 2 split in the middle of a workgroup's rows."""
+    from gpu_util import run_hip
+    from paper_2309_12307_amd import binding
+    B, N, H, Hkv, D, G = 1, 4608, 4, 2, 128, 2304
+    inp = inputs.make_inputs(B, N, H, Hkv, D, seed=184, dtype="bf16")
+    out = run_hip(inp, G, "bf16", wrap_variant=binding.WRAP_SPLIT)
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, variant2=True, dtype=np.float32)
+    compare(out, ref)
+    out = run_hip(inp, G, "bf16")
+    ref = orc.s2attn_fwd_bwd(inp["q"], inp["k"], inp["v"], inp["do"], G, dtype=np.float32)
+    compare(out, ref)
+
+
 def test_variant2_with_all_heads_shifted_and_head_shards():
     from gpu_util import run_hip
     from paper_2309_12307_amd import binding
