@@ -6,10 +6,10 @@
 // A workgroup (8 waves on one CU) owns 128 keys of one (batch, kv head, group) in the rolled
 // frame of the kv head's class (LongLoRA Algorithm 1: the shift is row addressing only) and
 // walks the 64-row query tiles at or below the diagonal (from the end of the group down to
-// the diagonal) for every query head of the kv head.  The four products of the softmax-Jacobian backward (dS = P * (dP - delta), P
-// recomputed from the stored log-sum-exp) are split between the two waves that share a
-// SIMD and a 32-key block, so that each fits in 256 registers with all accumulators in
-// ordinary vector registers:
+// the diagonal) for every query head of the kv head.  The four products of the
+// softmax-Jacobian backward (dS = P * (dP - delta), P recomputed from the stored
+// log-sum-exp) are split between the two waves that share a SIMD and a 32-key block, so that
+// each fits in 256 registers with all accumulators in ordinary vector registers:
 //   wave A (0-3):  S = Q K^T,  P = exp2(c S - lse2)  ->  LDS (fp32),   dV^T += dO^T P
 //   wave B (4-7):  delta - dP = delta - dO V^T,  P <- LDS,  dS = P (dP - delta),  dK^T += Q^T dS
 // B finishes tile n-1 (dS, dK) at the start of iteration n, after the barrier that also
