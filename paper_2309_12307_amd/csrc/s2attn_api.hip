@@ -140,11 +140,7 @@ int check_common(const s2attn_params* p, int backward) {
         (long long)p->head_offset + p->H > p->heads_total || p->head_offset % (p->H / p->Hkv) != 0)
       return S2ATTN_ERR_HEADS;
   }
-  if (p->dtype == S2ATTN_F32) {
-    if (p->D != 64 && p->D != 128) return S2ATTN_ERR_HEADDIM;
-  } else {
-    if (p->D != 64 && p->D != 128) return S2ATTN_ERR_HEADDIM;
-  }
+  if (p->D != 64 && p->D != 128) return S2ATTN_ERR_HEADDIM;
   // grid z carries batch * heads (* 2 classes); element offsets are 64-bit
   if ((long long)p->B * p->H * 2 > 65535 || (long long)p->N / p->G > 65535) return S2ATTN_ERR_TOO_LARGE;
   if ((double)p->B * p->N * p->H * p->D > 9.0e18 / 4) return S2ATTN_ERR_TOO_LARGE;

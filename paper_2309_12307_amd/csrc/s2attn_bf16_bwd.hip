@@ -271,7 +271,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
   const uint32_t do_lane = (uint32_t)(st_row * do_row_bytes) + st_chunk;
   const uint64_t q_batch = uni64(reinterpret_cast<uint64_t>(qp) + (uint64_t)b * a.sq.b * 2);
   const uint64_t do_batch = uni64(reinterpret_cast<uint64_t>(dop) + (uint64_t)b * a.so.b * 2);
-  auto issue_tile = [&](int hh, int it, int stage) {
+  auto issue_tile = [&](int hh, int it, int stage) __attribute__((always_inline)) {
     const int h = h_lo + hh;
     const int q0 = (it_begin + it) * kQTileRows;
     const uint32_t qs = smem_base + stage * 2 * kQTileBytes + 4 * w * kRowBytes;
@@ -291,7 +291,7 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
           dma4s(reinterpret_cast<uint64_t>(a.lse2) + ro, lane * 4, rows_base + ((stage * 2 + 0) * kQTileRows + 64 * hf) * 4);
           dma4s(reinterpret_cast<uint64_t>(a.delta) + ro, lane * 4, rows_base + ((stage * 2 + 1) * kQTileRows + 64 * hf) * 4);
         }
-      } else {   // every row finds its own token; padding rows repeat the last row of the group
+      } else {   // every row finds its own token; padding rows repeat the last row of the run
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const int tok = run_token(a, run, q0 + 64 * hf + 16 * p + st_row, s);
@@ -315,15 +315,16 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
 #pragma unroll
   for (int db = 0; db < 4; ++db) { dk_acc[db] = zero16(); dv_acc[db] = zero16(); }
 
-  // Tile n = hh * nq + it is query tile it_begin + it of head h_lo + hh.  Waits for its
-  // staged data, starts the staging of tile n + 1 into the other stage and describes the tile.
-  auto begin_tile = [&](int n, int hh, int it) {
+  // The n-th tile of the walk is query tile it_begin + it of head h_lo + hh.  Waits for its
+  // staged data, starts the staging of the next one (the next head of the same query tile,
+  // else the first head of the tile before) into the other stage and describes the tile.
+  auto begin_tile = [&](int n, int hh, int it) __attribute__((always_inline)) {
     const int stage = n & 1;
     wait_vmcnt0();
     __syncthreads();
     if (n + 1 < n_iter) {
-      const bool wrap = it + 1 == nq;
-      issue_tile(wrap ? hh + 1 : hh, wrap ? 0 : it + 1, stage ^ 1);
+      const bool wrap = hh + 1 == nheads;
+      issue_tile(wrap ? 0 : hh + 1, wrap ? it - 1 : it, stage ^ 1);
     }
     if constexpr (RAGGED) __builtin_amdgcn_sched_barrier(0);   // keeps the per-row addresses out of the tile body
     DkdvTile t;
@@ -335,28 +336,25 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
     return t;
   };
 
-  // Per head: the diagonal tile first, then the interior tiles in a loop of their own (the
-  // hot loop holds nothing but the pipelined interior tile), then, for a group size that is
-  // not a multiple of the tile, the partial last tile.
+  // Query tiles from the end of the run down to the diagonal, the heads of the kv head
+  // innermost: workgroups of one (group, class) that hold different key tiles then ask for
+  // the same Q / dO tile at about the same time, whatever their number of tiles, and the L2
+  // serves all but the first.  The partial last tile (a group size that is not a multiple of
+  // the tile) comes first, the interior tiles follow in a loop of their own (the hot loop
+  // holds nothing but the pipelined interior tile), the diagonal tiles come last.
   const bool has_tail = RAGGED && (run.len % kQTileRows != 0);
   const int n_full = has_tail ? nq - 1 : nq;           // tiles [0, n_full) are complete
-  if (n_iter > 0) issue_tile(0, 0, 0);
+  if (n_iter > 0) issue_tile(0, nq - 1, 0);
   int n = 0;
-  for (int hh = 0; hh < nheads; ++hh) {
-    {
-      const DkdvTile t = begin_tile(n, hh, 0);
-      if constexpr (RAGGED) {
-        // query rows >= G (padding of a partial tile) give P = 0; blocks before this wave's
-        // keys are skipped
-        for (int mb = w; mb < 4; ++mb) dkdv_block<true, DH>(t, mb, j0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, run.len);
-      } else {
-        // block mb < w is entirely before this wave's keys, block w is masked
-        dkdv_block<true>(t, w, j0 + 32 * w, key, kf, vf, dk_acc, dv_acc);
-        for (int mb = w + 1; mb < 4; ++mb) dkdv_block<false>(t, mb, 0, key, kf, vf, dk_acc, dv_acc);
-      }
-      ++n;
+  if (has_tail && nq > 1) {
+    const int q0 = j0 + (nq - 1) * kQTileRows;
+    for (int hh = 0; hh < nheads; ++hh, ++n) {
+      const DkdvTile t = begin_tile(n, hh, nq - 1);
+      for (int mb = 0; mb < 4; ++mb) dkdv_block<true, DH>(t, mb, q0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, run.len);
     }
-    for (int it = 1; it < n_full; ++it, ++n) {
+  }
+  for (int it = n_full - 1; it >= 1; --it) {
+    for (int hh = 0; hh < nheads; ++hh, ++n) {
       const DkdvTile t = begin_tile(n, hh, it);
       if constexpr (DH == 128) {
         dkdv_interior_tile(t, kf, vf, dk_acc, dv_acc);
@@ -364,11 +362,17 @@ bwd_dkdv_bf16_kernel(KArgs a, int ncls, int T, int il, int n_rest) {
         for (int mb = 0; mb < 4; ++mb) dkdv_block<false, DH>(t, mb, 0, key, kf, vf, dk_acc, dv_acc);
       }
     }
-    if (has_tail && nq > 1) {
-      const DkdvTile t = begin_tile(n, hh, nq - 1);
-      const int q0 = j0 + (nq - 1) * kQTileRows;
-      for (int mb = 0; mb < 4; ++mb) dkdv_block<true, DH>(t, mb, q0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, run.len);
-      ++n;
+  }
+  for (int hh = 0; hh < nheads; ++hh, ++n) {
+    const DkdvTile t = begin_tile(n, hh, 0);
+    if constexpr (RAGGED) {
+      // query rows >= G (padding of a partial tile) give P = 0; blocks before this wave's
+      // keys are skipped
+      for (int mb = w; mb < 4; ++mb) dkdv_block<true, DH>(t, mb, j0 + 32 * mb, key, kf, vf, dk_acc, dv_acc, run.len);
+    } else {
+      // block mb < w is entirely before this wave's keys, block w is masked
+      dkdv_block<true>(t, w, j0 + 32 * w, key, kf, vf, dk_acc, dv_acc);
+      for (int mb = w + 1; mb < 4; ++mb) dkdv_block<false>(t, mb, 0, key, kf, vf, dk_acc, dv_acc);
     }
   }
   __syncthreads();
