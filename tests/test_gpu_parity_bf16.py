@@ -37,6 +37,7 @@ SHAPES = [
     (1, 768, 2, 1, 128, 256),      # MQA: the kv head serves both classes
     (1, 1536, 6, 3, 128, 512),     # odd Hkv: middle kv head is mixed
     (1, 640, 2, 2, 128, 640),      # one group, 5 tiles
+    (1, 1024, 8, 1, 128, 512),     # MQA, four query heads per class walked tile by tile
 ]
 
 
@@ -254,6 +255,7 @@ RAGGED_SHAPES = [
     (1, 4, 2, 2, 128, 2),          # smallest group: two tokens, shift 1
     (1, 24, 2, 1, 128, 6),
     (1, 130, 2, 2, 128, 130),      # one group whose second tile holds two rows
+    (1, 600, 8, 2, 128, 300),      # four query heads per kv head, three tiles, the last partial
 ]
 
 
