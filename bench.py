@@ -161,8 +161,8 @@ def main():
     ap.add_argument("--steps", type=int, default=None,
                     help="timed steps (default 20; 100 for C2, whose step is under a millisecond)")
     ap.add_argument("--warmup", type=int, default=None,
-                    help="untimed steps before them (default 5, about 45 ms of C3: the chip takes that long "
-                         "to reach its steady clock after an idle period; 60 for C2)")
+                    help="untimed steps before them (default 10, about 90 ms of C3: after an idle period the chip "
+                         "takes about 45 ms of load to reach its steady clock; 60 for C2)")
     ap.add_argument("--workload", default="C3",
                     help="C2 | C3 | C4 | C5 (bf16 configurations); a '-full' suffix (e.g. C3-full) runs plain "
                          "full causal attention of the same layer through the same kernels (G = N, no head "
@@ -193,7 +193,7 @@ def main():
     if args.steps is None:
         args.steps = 100 if short_step else 20
     if args.warmup is None:
-        args.warmup = 60 if short_step else 5
+        args.warmup = 60 if short_step else 10
     if args.gpus != 1:
         print("bench.py measures the single-GPU S2-Attn kernels only: this build has no multi-GPU path "
               "(--gpus must be 1)", file=sys.stderr)
